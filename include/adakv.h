@@ -1,0 +1,165 @@
+/*
+ * adakv.h -- C ABI of the MI355X (gfx950) Ada-KV per-layer cache compression library.
+ *
+ * The library runs the compression step the paper performs on every attention layer at the
+ * end of prefill (Section 4.1, "Parameters"): Algorithm 2 ("Ada-SnapKV/Ada-Pyramid in One
+ * Layer") with Algorithm 1 ("Adaptive Budget Allocation") inside it, as four calls:
+ *
+ *     adakv_score     Alg. 2 lines 1-5   observation-window attention scores of every prefix key
+ *     adakv_allocate  Alg. 2 lines 6-8   layer-wide Top-B' -> per-head budgets (Alg. 1) + safeguard
+ *     adakv_select    Alg. 2 line 9      per-head Top-B_i eviction decision, as index lists
+ *     adakv_compact   Alg. 2 lines 10-11 gather of the retained K/V rows into the flattened
+ *                                        variable-length per-head cache (Section 3.5)
+ *
+ * Notation (paper's where it has one):
+ *     n      cache elements OUTSIDE the observation window = eviction candidates of a sequence
+ *     w      observation window size; a sequence owns N = n + w rows of q/K/V, window last
+ *     h_kv   KV heads; h_q query heads, g = h_q / h_kv of them share a KV head.  Scores,
+ *            budgets and outputs are per KV head (Section 3.5: group-mean criterion)
+ *     B      layer budget of a sequence INCLUDING its w window rows per head (Alg. 2 l.6)
+ *     B'     B - w*h_kv, the part Algorithm 1 distributes
+ *     alpha  safeguard hyper-parameter: share of B' handed out uniformly.  alpha = 1 is the
+ *            uniform allocation B'/h of Section 3.2, alpha = 0 is Algorithm 1 unmodified
+ *     k      max-pool kernel (Section 4.1: 7)
+ *
+ * General rules
+ *   - Every pointer marked (device) is device memory on the current HIP device; (host) is
+ *     ordinary host memory that is read during the call and may be reused on return.
+ *   - The caller owns every buffer.  The library allocates nothing, frees nothing and keeps
+ *     no state between calls; scratch memory comes in through `ws` (size from
+ *     adakv_workspace_bytes; its contents need not survive from one call to the next).
+ *   - Every call only enqueues kernels on `hip_stream` (a hipStream_t, NULL = default stream)
+ *     and returns; nothing synchronises with the host.  The number of output rows, sum_b B_b,
+ *     is known before the call, so outputs are pre-sized by the caller.
+ *   - Return value: ADAKV_OK or a negative adakv_status.  On ADAKV_EINVAL, ADAKV_EUNSUPPORTED
+ *     and ADAKV_EWORKSPACE nothing was launched and outputs are untouched.
+ *   - Calls that share a workspace or an output buffer must be ordered on one stream.
+ */
+#ifndef ADAKV_H
+#define ADAKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { ADAKV_BF16 = 0, ADAKV_FP32 = 1 } adakv_dtype;
+
+typedef enum {
+  ADAKV_OK = 0,
+  ADAKV_EINVAL = -1,       /* NULL required pointer, or a parameter outside its domain      */
+  ADAKV_EUNSUPPORTED = -2, /* valid problem, but a shape/dtype this build has no kernel for  */
+  ADAKV_EWORKSPACE = -3,   /* ws == NULL or ws_bytes < adakv_workspace_bytes(L)              */
+  ADAKV_EHIP = -4          /* a HIP runtime call failed (kernel launch)                      */
+} adakv_status;
+
+#define ADAKV_MAX_BATCH 64          /* sequences per call                                    */
+#define ADAKV_FLAG_ROW_LSE 1u       /* bit 0 of flags: informational, set by callers that
+                                       pass row_lse to adakv_score                           */
+
+/*
+ * One attention layer's compression problem, for `batch` independent sequences (Algorithm 1
+ * acts "within a single layer" of one sequence, so budgets never move between sequences).
+ *
+ * Domain (else ADAKV_EINVAL): h_q % h_kv == 0; w >= 1; pool_k odd >= 1; 0 <= alpha <= 1;
+ * 1 <= batch <= ADAKV_MAX_BATCH; n[b] >= 1; w*h_kv <= B[b] <= w*h_kv + h_kv*n[b];
+ * tok_off non-decreasing with tok_off[b+1] - tok_off[b] >= n[b] + w.
+ * Supported (else ADAKV_EUNSUPPORTED): d in {64, 128}; dtype bf16 or fp32; sum_b h_kv*n[b]
+ * and sum_b B[b] below 2^31.
+ */
+typedef struct {
+  int32_t dtype;            /* adakv_dtype of q_window, K, V, K_out, V_out                  */
+  int32_t h_q, h_kv, d;     /* query head hq belongs to KV head hq / (h_q / h_kv)           */
+  int32_t w, pool_k;
+  float alpha;
+  float scale;              /* logit scale; 0 means 1/sqrt(d)                               */
+  int32_t batch;
+  const int32_t *n;         /* (host) [batch]  prefix length per sequence                   */
+  const int32_t *B;         /* (host) [batch]  layer budget per sequence, window included   */
+  const int64_t *tok_off;   /* (host) [batch+1] first K/V row of each sequence; NULL means
+                               batch == 1 at row 0                                          */
+  int64_t k_stride_tok, k_stride_head; /* K element strides; the d axis is contiguous       */
+  int64_t v_stride_tok, v_stride_head; /* same for V                                        */
+  uint32_t flags;
+} adakv_layer;
+
+/* Scratch bytes that any of the four calls may need for this problem (0 on invalid L). */
+size_t adakv_workspace_bytes(const adakv_layer *L);
+
+/* Static, never NULL. */
+const char *adakv_strerror(int status);
+
+/*
+ * Alg. 2 lines 1-5 and Section 3.5.  For every sequence b, KV head c and prefix position j:
+ *
+ *   scores[off_b + c*n_b + j] = max over |j' - j| <= k/2, 0 <= j' < n_b of
+ *        (1/(g*w)) * sum over the g query heads hq of c and the w window rows r of
+ *        exp(scale * q_window[b][hq][r] . K[tok_off[b] + j'][c]  -  lse[b][hq][r])
+ *
+ * with off_b = h_kv * sum_{b'<b} n_b'.  lse[b][hq][r] is row_lse if given; otherwise it is
+ * the natural log of the sum over the n_b prefix keys of exp(scaled logit), i.e. the softmax
+ * of Alg. 2 l.3 runs over the cache outside the window.  A caller that passes the prefill
+ * attention's own log-sum-exp gets the normalisation over every visible key instead.
+ * Logits are accumulated in fp32, softmax and reductions are fp32, the mean is taken before
+ * the pool, and the pool is stride 1, same length, clipped at both ends.
+ *
+ *   q_window (device) [batch][h_q][w][d], contiguous, L->dtype
+ *   K        (device) rows tok_off[b] .. tok_off[b]+n_b-1 are read, element (row, c, e) at
+ *                     row*k_stride_tok + c*k_stride_head + e; rows must be 16-byte aligned
+ *   row_lse  (device) [batch][h_q][w] fp32, or NULL
+ *   scores   (device) [sum_b h_kv*n_b] fp32, written
+ */
+int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const float *row_lse,
+                float *scores, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Alg. 2 lines 6-8 with Algorithm 1.  Per sequence: B' = B - w*h_kv; the B' largest of the
+ * h_kv*n scores are found (ties: lower flat index c*n + j first) and counted per head, f_c;
+ * the safeguard mixes in the uniform share, x_c = (1-alpha) f_c + alpha B'/h_kv, in exact
+ * integer arithmetic with alpha rounded to 16 fractional bits:
+ *     num_c = (65536-a) h_kv f_c + a B',  den = 65536 h_kv,  budgets[c] = floor(num_c/den),
+ * and the B' - sum floor units left go to the heads with the largest num_c % den (ties: lower
+ * c), so sum_c budgets[c] = B' exactly.  Scores must be >= 0 and not NaN.
+ *
+ *   scores     (device) as written by adakv_score
+ *   budgets    (device) [batch*h_kv] int32, written: prefix rows kept per (b, c)
+ *   cu_seqlens (device) [batch*h_kv+1] int32, written: cu[0] = 0,
+ *                       cu[s+1] = cu[s] + budgets[s] + w, segment s = b*h_kv + c
+ */
+int adakv_allocate(const adakv_layer *L, const float *scores, int32_t *budgets,
+                   int32_t *cu_seqlens, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Alg. 2 line 9 (the Top-k eviction decision of Section 3.2) as index lists.  Segment
+ * s = (b, c) of `indices` starts at cu_seqlens[s] and holds the budgets[s] prefix positions
+ * of head c with the largest scores (ties: lower position first) in ascending order, followed
+ * by the window positions n_b .. n_b+w-1.  Positions count from the sequence's first row.
+ *
+ *   scores, budgets, cu_seqlens (device) as above; budgets[s] <= n_b and cu_seqlens must be
+ *                               the running sum of budgets + w (not checked)
+ *   indices (device) [sum_b B_b] int32, written
+ */
+int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budgets,
+                 const int32_t *cu_seqlens, int32_t *indices, void *ws, size_t ws_bytes,
+                 void *hip_stream);
+
+/*
+ * Alg. 2 lines 10-11 into the flattened layout of Section 3.5: for segment s = (b, c) and
+ * cu_seqlens[s] <= t < cu_seqlens[s+1],
+ *     K_out[t][:] = K[tok_off[b] + indices[t]][c][:],   V_out likewise.
+ * Pure byte copy.
+ *
+ *   K, V           (device) strided as in the layer; rows 16-byte aligned
+ *   indices        (device) [sum_b B_b] int32, each in [0, n_b + w)  (not checked)
+ *   cu_seqlens     (device) [batch*h_kv+1] int32 with cu[last] = sum_b B_b
+ *   K_out, V_out   (device) [sum_b B_b][d] contiguous, L->dtype, written; 16-byte aligned
+ */
+int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int32_t *indices,
+                  const int32_t *cu_seqlens, void *K_out, void *V_out, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAKV_H */

@@ -1,0 +1,214 @@
+"""ctypes binding of libadakv.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI (include/adakv.h).
+PyTorch is used for device memory and for the stream handle, nothing else.  There is
+no fallback: if the library is missing, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "lib", "libadakv.so")
+_lib = None
+
+ADAKV_BF16, ADAKV_FP32 = 0, 1
+MAX_BATCH = 64
+
+
+class AdaKVError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = load_library().adakv_strerror(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class _CLayer(ctypes.Structure):
+    _fields_ = [
+        ("dtype", ctypes.c_int32), ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32),
+        ("d", ctypes.c_int32), ("w", ctypes.c_int32), ("pool_k", ctypes.c_int32),
+        ("alpha", ctypes.c_float), ("scale", ctypes.c_float), ("batch", ctypes.c_int32),
+        ("n", ctypes.POINTER(ctypes.c_int32)), ("B", ctypes.POINTER(ctypes.c_int32)),
+        ("tok_off", ctypes.POINTER(ctypes.c_int64)),
+        ("k_stride_tok", ctypes.c_int64), ("k_stride_head", ctypes.c_int64),
+        ("v_stride_tok", ctypes.c_int64), ("v_stride_head", ctypes.c_int64),
+        ("flags", ctypes.c_uint32),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libadakv.so (built by __graft_entry__.build()).  Raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it first "
+                           "(python -c 'import __graft_entry__ as g; g.build()'); "
+                           "there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, V, Z = ctypes.POINTER(_CLayer), ctypes.c_void_p, ctypes.c_size_t
+    lib.adakv_workspace_bytes.restype = Z
+    lib.adakv_workspace_bytes.argtypes = [P]
+    lib.adakv_strerror.restype = ctypes.c_char_p
+    lib.adakv_strerror.argtypes = [ctypes.c_int]
+    for name, args in (("adakv_score", [P, V, V, V, V, V, Z, V]),
+                       ("adakv_allocate", [P, V, V, V, V, Z, V]),
+                       ("adakv_select", [P, V, V, V, V, V, Z, V]),
+                       ("adakv_compact", [P, V, V, V, V, V, V, V])):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+class Layer:
+    """Host-side description of one layer's compression problem (adakv_layer)."""
+
+    def __init__(self, dtype, h_q, h_kv, d, w, pool_k, alpha, n, B, tok_off=None, scale=0.0,
+                 k_strides=None, v_strides=None, flags=0):
+        self.torch_dtype = dtype
+        self.h_q, self.h_kv, self.d, self.w, self.pool_k = h_q, h_kv, d, w, pool_k
+        self.alpha, self.scale = float(alpha), float(scale)
+        self.n = [int(v) for v in (n if isinstance(n, (list, tuple)) else [n])]
+        self.B = [int(v) for v in (B if isinstance(B, (list, tuple)) else [B])]
+        self.batch = len(self.n)
+        if tok_off is None:
+            tok_off = [0]
+            for nb in self.n:
+                tok_off.append(tok_off[-1] + nb + w)
+        self.tok_off = [int(v) for v in tok_off]
+        self._n = (ctypes.c_int32 * self.batch)(*self.n)
+        self._B = (ctypes.c_int32 * len(self.B))(*self.B)
+        self._off = (ctypes.c_int64 * len(self.tok_off))(*self.tok_off)
+        ks = k_strides or (h_kv * d, d)
+        vs = v_strides or (h_kv * d, d)
+        code = {torch.bfloat16: ADAKV_BF16, torch.float32: ADAKV_FP32}.get(dtype, 99)
+        self.c = _CLayer(code, h_q, h_kv, d, w, pool_k, self.alpha, self.scale, self.batch,
+                         self._n, self._B, self._off, ks[0], ks[1], vs[0], vs[1], flags)
+
+    @classmethod
+    def from_workload(cls, wl, **kw):
+        return cls(wl.dtype, wl.h_q, wl.h_kv, wl.d, wl.w, wl.pool_k, wl.alpha, wl.n, wl.B,
+                   tok_off=wl.tok_off, **kw)
+
+    @property
+    def num_scores(self):
+        return self.h_kv * sum(self.n)
+
+    @property
+    def num_rows_out(self):
+        return sum(self.B)
+
+    @property
+    def num_segments(self):
+        return self.batch * self.h_kv
+
+
+def workspace_bytes(layer: Layer) -> int:
+    return int(load_library().adakv_workspace_bytes(ctypes.byref(layer.c)))
+
+
+def _ptr(t, name, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _workspace(layer, ws):
+    if ws is None:
+        ws = torch.empty(max(workspace_bytes(layer), 16), dtype=torch.uint8, device="cuda")
+    return ws, ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel())
+
+
+def score(layer: Layer, q_window, K, row_lse=None, out=None, ws=None, stream=None):
+    """adakv_score: eviction scores [sum_b h_kv*n_b] fp32 (sequence-major, then head)."""
+    lib = load_library()
+    if not q_window.is_contiguous():
+        raise ValueError("q_window must be contiguous")
+    if out is None:
+        out = torch.empty(layer.num_scores, dtype=torch.float32, device=K.device)
+    ws, wp, wn = _workspace(layer, ws)
+    st = lib.adakv_score(ctypes.byref(layer.c), _ptr(q_window, "q_window", layer.torch_dtype),
+                         _ptr(K, "K", layer.torch_dtype), _ptr(row_lse, "row_lse", torch.float32),
+                         _ptr(out, "scores", torch.float32), wp, wn, _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_score")
+    return out
+
+
+def allocate(layer: Layer, scores, budgets=None, cu_seqlens=None, ws=None, stream=None):
+    """adakv_allocate: budgets [batch*h_kv] and cu_seqlens [batch*h_kv+1], int32."""
+    lib = load_library()
+    if budgets is None:
+        budgets = torch.empty(layer.num_segments, dtype=torch.int32, device=scores.device)
+    if cu_seqlens is None:
+        cu_seqlens = torch.empty(layer.num_segments + 1, dtype=torch.int32, device=scores.device)
+    ws, wp, wn = _workspace(layer, ws)
+    st = lib.adakv_allocate(ctypes.byref(layer.c), _ptr(scores, "scores", torch.float32),
+                            _ptr(budgets, "budgets", torch.int32),
+                            _ptr(cu_seqlens, "cu_seqlens", torch.int32), wp, wn, _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_allocate")
+    return budgets, cu_seqlens
+
+
+def select(layer: Layer, scores, budgets, cu_seqlens, indices=None, ws=None, stream=None):
+    """adakv_select: retained positions [sum_b B_b] int32, flattened by (sequence, head)."""
+    lib = load_library()
+    if indices is None:
+        indices = torch.empty(layer.num_rows_out, dtype=torch.int32, device=scores.device)
+    ws, wp, wn = _workspace(layer, ws)
+    st = lib.adakv_select(ctypes.byref(layer.c), _ptr(scores, "scores", torch.float32),
+                          _ptr(budgets, "budgets", torch.int32),
+                          _ptr(cu_seqlens, "cu_seqlens", torch.int32),
+                          _ptr(indices, "indices", torch.int32), wp, wn, _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_select")
+    return indices
+
+
+def compact(layer: Layer, K, V, indices, cu_seqlens, K_out=None, V_out=None, stream=None):
+    """adakv_compact: K_out, V_out [sum_b B_b, d] in the layer's dtype."""
+    lib = load_library()
+    if K_out is None:
+        K_out = torch.empty((layer.num_rows_out, layer.d), dtype=layer.torch_dtype, device=K.device)
+    if V_out is None:
+        V_out = torch.empty((layer.num_rows_out, layer.d), dtype=layer.torch_dtype, device=K.device)
+    st = lib.adakv_compact(ctypes.byref(layer.c), _ptr(K, "K", layer.torch_dtype),
+                           _ptr(V, "V", layer.torch_dtype), _ptr(indices, "indices", torch.int32),
+                           _ptr(cu_seqlens, "cu_seqlens", torch.int32),
+                           _ptr(K_out, "K_out", layer.torch_dtype),
+                           _ptr(V_out, "V_out", layer.torch_dtype), _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_compact")
+    return K_out, V_out
+
+
+def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, bufs=None):
+    """The whole step: the four calls back to back on one stream, no host synchronisation.
+    `bufs` may carry pre-allocated outputs (scores, budgets, cu_seqlens, indices, K_out, V_out)."""
+    b = bufs or {}
+    if ws is None:
+        ws = torch.empty(max(workspace_bytes(layer), 16), dtype=torch.uint8, device=K.device)
+    sc = score(layer, q_window, K, row_lse=row_lse, out=b.get("scores"), ws=ws, stream=stream)
+    bud, cu = allocate(layer, sc, b.get("budgets"), b.get("cu_seqlens"), ws=ws, stream=stream)
+    idx = select(layer, sc, bud, cu, b.get("indices"), ws=ws, stream=stream)
+    K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
+    return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
