@@ -152,7 +152,7 @@ int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budge
  * Pure byte copy.
  *
  *   K, V           (device) strided as in the layer; rows 16-byte aligned
- *   indices        (device) [sum_b B_b] int32, each in [0, n_b + w)  (not checked)
+ *   indices        (device) [sum_b B_b] int32, each in [0, n_b + w)  (values outside are clamped)
  *   cu_seqlens     (device) [batch*h_kv+1] int32 with cu[last] = sum_b B_b
  *   K_out, V_out   (device) [sum_b B_b][d] contiguous, L->dtype, written; 16-byte aligned
  */

@@ -1,0 +1,34 @@
+"""Builds libadakv.so for gfx950 with hipcc (cross-compiles without a GPU)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "select.hip", "compact.hip"]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         # packed-fp32 VALU forms are kept out of the generated code on purpose
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-function"]
+
+
+def build(verbose: bool = False, extra_flags=()) -> str:
+    out_dir = os.path.join(HERE, "lib")
+    os.makedirs(out_dir, exist_ok=True)
+    out = os.path.join(out_dir, "libadakv.so")
+    cmd = (["hipcc"] + FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(HERE, "csrc")]
+           + [os.path.join(HERE, "csrc", s) for s in SOURCES] + ["-o", out])
+    if verbose:
+        print(" ".join(cmd))
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stdout + r.stderr)
+    if verbose and r.stderr.strip():
+        print(r.stderr)
+    return out
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,152 @@
+// C ABI entry points: argument checks, workspace planning, kernel launches.
+// Each call only enqueues work on the caller's stream.
+#include <math.h>
+
+#include "common.h"
+
+namespace adakv {
+
+static int build_tables(const adakv_layer *L, SeqTab &st, Dims &dm) {
+  if (!L || !L->n || !L->B) return ADAKV_EINVAL;
+  if (L->h_q < 1 || L->h_kv < 1 || L->h_q % L->h_kv != 0) return ADAKV_EINVAL;
+  if (L->w < 1 || L->pool_k < 1 || L->pool_k % 2 == 0) return ADAKV_EINVAL;
+  if (!(L->alpha >= 0.0f && L->alpha <= 1.0f)) return ADAKV_EINVAL;
+  if (!(L->scale >= 0.0f) || isinf(L->scale)) return ADAKV_EINVAL;
+  if (L->batch < 1 || L->batch > ADAKV_MAX_BATCH) return ADAKV_EINVAL;
+  if (L->batch > 1 && !L->tok_off) return ADAKV_EINVAL;
+  if (L->d < 1) return ADAKV_EINVAL;
+  long long sc = 0, out = 0;
+  st.batch = L->batch;
+  for (int b = 0; b < L->batch; ++b) {
+    long long n = L->n[b], B = L->B[b];
+    long long wh = (long long)L->w * L->h_kv;
+    if (n < 1 || B < wh || B - wh > (long long)L->h_kv * n) return ADAKV_EINVAL;
+    long long t0 = L->tok_off ? L->tok_off[b] : 0;
+    if (t0 < 0) return ADAKV_EINVAL;
+    if (L->tok_off && L->tok_off[b + 1] - t0 < n + L->w) return ADAKV_EINVAL;
+    st.n[b] = (int)n;
+    st.Bp[b] = (int)(B - wh);
+    st.tok_off[b] = t0;
+    st.score_off[b] = (int)sc;
+    st.out_off[b] = (int)out;
+    sc += (long long)L->h_kv * n;
+    out += B;
+    if (sc >= (1ll << 31) || out >= (1ll << 31)) return ADAKV_EUNSUPPORTED;
+  }
+  for (int b = L->batch; b < ADAKV_MAX_BATCH; ++b) {
+    st.n[b] = 0; st.Bp[b] = 0; st.tok_off[b] = 0;
+  }
+  for (int b = L->batch; b <= ADAKV_MAX_BATCH; ++b) {
+    st.score_off[b] = (int)sc;
+    st.out_off[b] = (int)out;
+  }
+  if (L->dtype != ADAKV_BF16 && L->dtype != ADAKV_FP32) return ADAKV_EUNSUPPORTED;
+  if (L->d != 64 && L->d != 128) return ADAKV_EUNSUPPORTED;
+  if (L->h_kv > 64 || (long long)L->h_q * L->w > (1 << 20)) return ADAKV_EUNSUPPORTED;
+  const long long esz = L->dtype == ADAKV_BF16 ? 2 : 4;
+  const long long strides[4] = {L->k_stride_tok, L->k_stride_head, L->v_stride_tok,
+                                L->v_stride_head};
+  for (long long sd : strides) {
+    if (sd < L->d) return ADAKV_EINVAL;
+    if ((sd * esz) % 16 != 0) return ADAKV_EUNSUPPORTED;   // rows are moved as 16-byte words
+  }
+  dm.h_q = L->h_q; dm.h_kv = L->h_kv; dm.g = L->h_q / L->h_kv; dm.d = L->d; dm.w = L->w;
+  dm.pool_k = L->pool_k;
+  dm.scale = L->scale > 0.0f ? L->scale : 1.0f / sqrtf((float)L->d);
+  dm.alpha_fix = (int)floor((double)L->alpha * 65536.0 + 0.5);
+  dm.k_stride_tok = L->k_stride_tok; dm.k_stride_head = L->k_stride_head;
+  dm.v_stride_tok = L->v_stride_tok; dm.v_stride_head = L->v_stride_head;
+  return ADAKV_OK;
+}
+
+static size_t workspace_for(const SeqTab &st, const Dims &dm, int dtype) {
+  size_t a = plan_score(st, dm, dtype).total;
+  size_t b = plan_topk_bytes(st, dm);
+  return (a > b ? a : b) + 256;
+}
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace adakv
+
+using namespace adakv;
+
+extern "C" {
+
+size_t adakv_workspace_bytes(const adakv_layer *L) {
+  SeqTab st; Dims dm;
+  if (build_tables(L, st, dm) != ADAKV_OK) return 0;
+  return workspace_for(st, dm, L->dtype);
+}
+
+const char *adakv_strerror(int status) {
+  switch (status) {
+    case ADAKV_OK: return "ok";
+    case ADAKV_EINVAL: return "invalid argument (NULL pointer or parameter outside its domain)";
+    case ADAKV_EUNSUPPORTED: return "shape, dtype or alignment not supported by this build";
+    case ADAKV_EWORKSPACE: return "workspace missing or smaller than adakv_workspace_bytes";
+    case ADAKV_EHIP: return "a HIP runtime call failed";
+    default: return "unknown status";
+  }
+}
+
+int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const float *row_lse,
+                float *scores, void *ws, size_t ws_bytes, void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if (!q_window || !K || !scores) return ADAKV_EINVAL;
+  if (!aligned16(q_window) || !aligned16(K) || !aligned16(scores)) return ADAKV_EUNSUPPORTED;
+  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
+  ScorePlan pl = plan_score(st, dm, L->dtype);
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = mfma_path_supported(dm, L->dtype)
+                     ? launch_score_mfma(st, dm, q_window, K, row_lse, scores, wsp, pl, s)
+                     : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
+                                            pl, s);
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+int adakv_allocate(const adakv_layer *L, const float *scores, int32_t *budgets,
+                   int32_t *cu_seqlens, void *ws, size_t ws_bytes, void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if (!scores || !budgets || !cu_seqlens) return ADAKV_EINVAL;
+  if (!aligned16(scores)) return ADAKV_EUNSUPPORTED;
+  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
+  hipError_t e = launch_allocate(st, dm, scores, budgets, cu_seqlens, wsp, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budgets,
+                 const int32_t *cu_seqlens, int32_t *indices, void *ws, size_t ws_bytes,
+                 void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if (!scores || !budgets || !cu_seqlens || !indices) return ADAKV_EINVAL;
+  if (!aligned16(scores)) return ADAKV_EUNSUPPORTED;
+  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
+  hipError_t e = launch_select(st, dm, scores, budgets, cu_seqlens, indices, wsp,
+                               (hipStream_t)hip_stream);
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int32_t *indices,
+                  const int32_t *cu_seqlens, void *K_out, void *V_out, void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if (!K || !V || !indices || !cu_seqlens || !K_out || !V_out) return ADAKV_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out))
+    return ADAKV_EUNSUPPORTED;
+  hipError_t e = launch_compact(st, dm, L->dtype, K, V, indices, cu_seqlens, K_out, V_out,
+                                (hipStream_t)hip_stream);
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+}  // extern "C"

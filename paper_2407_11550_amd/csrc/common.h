@@ -1,0 +1,87 @@
+// Internal declarations shared by the translation units of libadakv.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "adakv.h"
+
+namespace adakv {
+
+// Per-sequence facts, passed to kernels by value (kernel argument segment): the layer
+// struct's host arrays never have to be copied to the device.
+struct SeqTab {
+  int batch;
+  int n[ADAKV_MAX_BATCH];               // prefix length
+  int Bp[ADAKV_MAX_BATCH];              // B' = B - w*h_kv
+  long long tok_off[ADAKV_MAX_BATCH];   // first K/V row
+  int score_off[ADAKV_MAX_BATCH + 1];   // h_kv * sum of earlier n: start of the sequence's scores
+  int out_off[ADAKV_MAX_BATCH + 1];     // sum of earlier B: start of the sequence's output rows
+};
+
+// Start of each sequence's run of blocks along grid.x when a kernel cuts every sequence
+// into fixed-size chunks of positions.
+struct ChunkTab {
+  int off[ADAKV_MAX_BATCH + 1];
+};
+
+inline ChunkTab make_chunks(const SeqTab &st, int chunk) {
+  ChunkTab ct;
+  ct.off[0] = 0;
+  for (int b = 0; b < st.batch; ++b) ct.off[b + 1] = ct.off[b] + (st.n[b] + chunk - 1) / chunk;
+  for (int b = st.batch + 1; b <= ADAKV_MAX_BATCH; ++b) ct.off[b] = ct.off[st.batch];
+  return ct;
+}
+
+__device__ __forceinline__ int find_seq(const ChunkTab &ct, int batch, int blk) {
+  int b = 0;
+  while (b + 1 < batch && blk >= ct.off[b + 1]) ++b;
+  return b;
+}
+
+struct Dims {
+  int h_q, h_kv, g, d, w, pool_k;
+  float scale;      // logit scale actually applied
+  int alpha_fix;    // alpha in 16 fractional bits, rounded to nearest
+  long long k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+};
+
+constexpr int RADIX_BINS = 2048;   // 11-bit digits: passes take bits 31..21, 20..10, 9..0
+constexpr int SEL_CHUNK = 4096;    // positions per block in the histogram and emit kernels
+constexpr int GEN_CHUNK = 256;     // keys per block in the plain-FMA scoring kernels
+
+// ---- scoring (score_generic.hip, score_mfma.hip) ------------------------------------------
+struct ScorePlan {                  // byte offsets into the workspace
+  size_t part_m, part_l;            // [chunks][h_q*w] partial row max / sum of exp
+  size_t lse;                       // [batch][h_q][w]
+  size_t raw;                       // [num_scores] pre-pool scores
+  size_t total;
+  int part_chunk;                   // keys per partial-statistics chunk
+};
+ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype);
+bool mfma_path_supported(const Dims &dm, int dtype);
+
+hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, const void *q,
+                                const void *K, const float *row_lse, float *scores, char *ws,
+                                const ScorePlan &pl, hipStream_t s);
+hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
+                             const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
+                             hipStream_t s);
+
+// ---- allocation and selection (select.hip) --------------------------------------------------
+size_t plan_topk_bytes(const SeqTab &st, const Dims &dm);
+hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores, int *budgets,
+                           int *cu_seqlens, char *ws, hipStream_t s);
+hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
+                         const int *budgets, const int *cu_seqlens, int *indices, char *ws,
+                         hipStream_t s);
+
+// ---- compaction (compact.hip) ---------------------------------------------------------------
+hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const void *K,
+                          const void *V, const int *indices, const int *cu_seqlens, void *K_out,
+                          void *V_out, hipStream_t s);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace adakv

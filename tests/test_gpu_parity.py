@@ -1,0 +1,217 @@
+"""GPU parity: every C-ABI call against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_11550_amd as adakv
+from oracle import adakv_oracle as O
+from paper_2407_11550_amd import synth
+
+from parity_util import (assert_end_to_end_close, assert_exact_on_scores, assert_scores_close,
+                         oracle_layer, to_f64)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run(wl, q, K, V, **kw):
+    layer = adakv.Layer.from_workload(wl, **kw)
+    out = adakv.compress(layer, q, K, V)
+    torch.cuda.synchronize()
+    return layer, out
+
+
+def _check_all(wl, q, K, V, out):
+    row0 = 0
+    soff = 0
+    for b in range(wl.batch):
+        ref = oracle_layer(wl, q, K, V, b)
+        ns = wl.h_kv * wl.n[b]
+        sc = out["scores"][soff:soff + ns].cpu().numpy()
+        assert_scores_close(sc, ref["scores"], f"{wl.name} seq {b}")
+        assert_exact_on_scores(out, sc, wl, K, V, b, seg0=b * wl.h_kv, row0=row0)
+        assert_end_to_end_close(out, ref, wl, b, seg0=b * wl.h_kv, row0=row0)
+        row0 += wl.B[b]
+        soff += ns
+
+
+# ------------------------------------------------------------------ whole step, small shapes
+SHAPES = [
+    # h_q h_kv  d   w  k   n     B(per kv head incl. window)   dtype
+    (4, 4, 64, 8, 7, 1024, 128, torch.float32),       # the tiny config's shape
+    (8, 2, 128, 32, 7, 3000, 300, torch.bfloat16),    # GQA 4, ragged tail
+    (32, 8, 128, 32, 7, 4099, 250, torch.bfloat16),   # Llama-3.1-8B heads, prime-ish length
+    (8, 8, 64, 16, 5, 777, 100, torch.bfloat16),      # d = 64, no GQA
+    (16, 2, 128, 64, 7, 2500, 400, torch.bfloat16),   # 70B-like group: g*w = 512 rows
+    (6, 2, 128, 8, 3, 513, 64, torch.float32),        # g = 3: rows not a multiple of 16
+    (4, 2, 64, 4, 1, 300, 50, torch.bfloat16),        # no pooling
+    (2, 1, 128, 1, 7, 5, 3, torch.bfloat16),          # n smaller than the pool kernel
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "hq%d_h%d_d%d_w%d_k%d_n%d_B%d_%s" % (s[:7] + (str(s[7])[6:],)))
+def test_whole_step_matches_oracle(shape):
+    h_q, h, d, w, k, n, Bh, dt = shape
+    _say(f"whole step {shape}")
+    wl = synth.small_workload(h_q, h, d, w, k, n, h * Bh, dtype=dt, seed=11)
+    q, K, V = synth.generate(wl, device=DEV)
+    _, out = _run(wl, q, K, V)
+    _check_all(wl, q, K, V, out)
+
+
+def test_tiny_config():
+    _say("tiny config")
+    wl = synth.workload("tiny")
+    q, K, V = synth.generate(wl, device=DEV)
+    _, out = _run(wl, q, K, V)
+    _check_all(wl, q, K, V, out)
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.2, 0.5, 1.0])
+def test_alpha_sweep(alpha):
+    _say(f"alpha {alpha}")
+    wl = synth.small_workload(8, 4, 128, 16, 7, 2048, 4 * 116, alpha=alpha, seed=5)
+    q, K, V = synth.generate(wl, device=DEV)
+    _, out = _run(wl, q, K, V)
+    _check_all(wl, q, K, V, out)
+    if alpha == 1.0:
+        assert out["budgets"].cpu().tolist() == [100] * 4
+
+
+def test_ragged_batch():
+    _say("ragged batch")
+    wl = synth.small_workload(8, 2, 128, 32, 7, [1500, 37, 4096, 600], [2 * 150, 2 * 40, 2 * 500, 2 * 32], seed=21)
+    q, K, V = synth.generate(wl, device=DEV)
+    _, out = _run(wl, q, K, V)
+    _check_all(wl, q, K, V, out)
+    assert int(out["cu_seqlens"][-1]) == sum(wl.B)
+
+
+def test_row_lse_input_gives_prefix_plus_window_normalisation():
+    _say("row_lse")
+    wl = synth.small_workload(8, 2, 128, 16, 7, 1200, 2 * 100, seed=31)
+    q, K, V = synth.generate(wl, device=DEV)
+    qd, Kd = to_f64(q[0]), to_f64(K)
+    n, w, d = wl.n[0], wl.w, wl.d
+    lse = np.empty((wl.h_q, w))
+    for hq in range(wl.h_q):
+        c = hq // wl.g
+        s = (qd[hq] @ Kd[:, c].T) / np.sqrt(d)
+        for r in range(w):
+            vis = np.concatenate([s[r, :n], s[r, n:n + r + 1]])
+            lse[hq, r] = vis.max() + np.log(np.exp(vis - vis.max()).sum())
+    layer = adakv.Layer.from_workload(wl, flags=1)
+    lse_t = torch.tensor(lse, dtype=torch.float32, device=DEV).reshape(1, wl.h_q, w)
+    sc = adakv.score(layer, q, K, row_lse=lse_t)
+    torch.cuda.synchronize()
+    ref = O.score(qd, Kd, n, w, wl.pool_k, norm="prefix+window")
+    # the fp32 rounding of lse itself moves every score of a row by up to |lse| * 2^-24
+    assert_scores_close(sc.cpu().numpy(), O.score(qd, Kd, n, w, wl.pool_k, row_lse=lse_t[0].double().cpu().numpy()), "row_lse")
+    np.testing.assert_allclose(sc.cpu().numpy().reshape(wl.h_kv, n), ref, rtol=2e-3)
+
+
+# ------------------------------------------------------- allocate / select on given scores
+def _alloc_select(scores_np, w, B, alpha):
+    h, n = scores_np.shape
+    layer = adakv.Layer(torch.bfloat16, h, h, 128, w, 7, alpha, [n], [B])
+    sc = torch.tensor(scores_np, device=DEV).reshape(-1)
+    bud, cu = adakv.allocate(layer, sc)
+    idx = adakv.select(layer, sc, bud, cu)
+    torch.cuda.synchronize()
+    return bud.cpu().numpy(), cu.cpu().numpy(), idx.cpu().numpy()
+
+
+@pytest.mark.parametrize("case", ["random", "quantised", "all_equal", "zeros_and_spikes", "plateaus"])
+@pytest.mark.parametrize("alpha", [0.0, 0.2, 1.0])
+def test_allocate_select_bit_exact_on_oracle_scores(case, alpha):
+    _say(f"allocate/select {case} alpha {alpha}")
+    rng = np.random.default_rng(3)
+    h, n, w = 4, 10007, 8
+    if case == "random":
+        s = rng.random((h, n)) ** np.array([1, 4, 16, 64])[:, None]
+    elif case == "quantised":
+        s = np.round(rng.random((h, n)) * 50) / 50
+    elif case == "all_equal":
+        s = np.full((h, n), 0.25)
+    elif case == "zeros_and_spikes":
+        s = np.zeros((h, n)); s[rng.integers(0, h, 300), rng.integers(0, n, 300)] = rng.random(300)
+    else:
+        s = O.max_pool_same(rng.random((h, n)) ** 8, 7)
+    s = s.astype(np.float32)
+    for B in (w * h, w * h + 1, w * h + 1000, w * h + h * n // 2, w * h + h * n - 1, w * h + h * n):
+        bud, cu, idx = _alloc_select(s, w, B, alpha)
+        rb, rcu = O.allocate(s, B, w, alpha)
+        assert np.array_equal(bud, rb), (case, B, bud, rb)
+        assert np.array_equal(cu, rcu)
+        assert np.array_equal(idx, O.select(s, rb, w)), (case, B)
+
+
+def test_select_with_zero_budget_heads_and_full_heads():
+    _say("select zero/full budgets")
+    rng = np.random.default_rng(4)
+    h, n, w = 3, 5000, 4
+    s = rng.random((h, n)).astype(np.float32)
+    budgets = np.array([0, n, 123], np.int32)
+    cu = np.concatenate([[0], np.cumsum(budgets + w)]).astype(np.int32)
+    layer = adakv.Layer(torch.bfloat16, h, h, 128, w, 7, 0.2, [n], [int(cu[-1])])
+    idx = adakv.select(layer, torch.tensor(s, device=DEV).reshape(-1), torch.tensor(budgets, device=DEV),
+                       torch.tensor(cu, device=DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), O.select(s, budgets, w))
+
+
+# ------------------------------------------------------------------------------ compaction
+@pytest.mark.parametrize("dt,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)])
+def test_compact_bit_exact_with_strides_and_canaries(dt, d):
+    _say(f"compact {dt} {d}")
+    g = torch.Generator(device=DEV); g.manual_seed(9)
+    h, n, w = 3, 700, 5
+    pad = 16
+    Kfull = torch.randn((n + w, h, d + pad), generator=g, device=DEV).to(dt)
+    Vfull = torch.randn((n + w, h + 1, d), generator=g, device=DEV).to(dt)
+    K, V = Kfull[:, :, :d], Vfull[:, :h, :]
+    rng = np.random.default_rng(9)
+    budgets = np.array([10, 0, 333], np.int32)
+    cu = np.concatenate([[0], np.cumsum(budgets + w)]).astype(np.int32)
+    s = rng.random((h, n)).astype(np.float32)
+    idx = O.select(s, budgets, w)
+    layer = adakv.Layer(dt, h, h, d, w, 7, 0.2, [n], [int(cu[-1])],
+                        k_strides=(h * (d + pad), d + pad), v_strides=((h + 1) * d, d))
+    rows = int(cu[-1])
+    Kbuf = torch.full((rows + 2, d), 7.0, device=DEV).to(dt)
+    Vbuf = torch.full((rows + 2, d), 7.0, device=DEV).to(dt)
+    adakv.compact(layer, K, V, torch.tensor(idx, device=DEV), torch.tensor(cu, device=DEV), Kbuf[1:-1], Vbuf[1:-1])
+    torch.cuda.synchronize()
+    Kr, Vr = O.compact(K.float().cpu().numpy(), V.float().cpu().numpy(), idx, cu)
+    assert np.array_equal(Kbuf[1:-1].float().cpu().numpy(), Kr)
+    assert np.array_equal(Vbuf[1:-1].float().cpu().numpy(), Vr)
+    for buf in (Kbuf, Vbuf):
+        assert torch.all(buf[0] == 7.0) and torch.all(buf[-1] == 7.0)      # canaries untouched
+
+
+# ------------------------------------------------------------------------------ determinism
+def test_two_runs_are_bit_identical():
+    _say("determinism")
+    wl = synth.small_workload(32, 8, 128, 32, 7, 9000, 8 * 300, seed=77)
+    q, K, V = synth.generate(wl, device=DEV)
+    _, a = _run(wl, q, K, V)
+    _, b = _run(wl, q, K, V)
+    for key in a:
+        assert torch.equal(a[key], b[key]), key
+
+
+# ------------------------------------------------------------------------------ full sizes
+@pytest.mark.parametrize("name", ["llama8b_32k", "llama8b_128k"])
+def test_full_size_layer(name):
+    _say(f"full size {name}")
+    wl = synth.workload(name)
+    q, K, V = synth.generate(wl, device=DEV)
+    _, out = _run(wl, q, K, V)
+    _say("  gpu done, oracle running")
+    _check_all(wl, q, K, V, out)
+    bud = out["budgets"].cpu().numpy()
+    _say(f"  budgets min {bud.min()} max {bud.max()}")

@@ -1,0 +1,88 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares, and
+rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2407_11550_amd as adakv
+from paper_2407_11550_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(adakv.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return adakv.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "adakv.h")).read()
+    names = set(re.findall(r"\b(adakv_[a-z_]+)\s*\(", header))
+    assert {"adakv_score", "adakv_allocate", "adakv_select", "adakv_compact",
+            "adakv_workspace_bytes", "adakv_strerror"} <= names
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_strerror(lib):
+    assert lib.adakv_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, 17):
+        assert len(lib.adakv_strerror(code)) > 0
+
+
+def _layer(**kw):
+    args = dict(dtype=torch.bfloat16, h_q=32, h_kv=8, d=128, w=32, pool_k=7, alpha=0.2,
+                n=[4096], B=[8 * 160])
+    args.update(kw)
+    return adakv.Layer(**args)
+
+
+def test_workspace_bytes(lib):
+    small, big = _layer(), _layer(n=[65536], B=[8 * 1024])
+    assert 0 < adakv.workspace_bytes(small) < adakv.workspace_bytes(big)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(h_q=30), dict(w=0), dict(pool_k=4), dict(alpha=1.5), dict(alpha=-0.1),
+    dict(B=[8 * 32 - 1]), dict(B=[8 * 32 + 8 * 4096 + 1]), dict(n=[0]),
+    dict(n=[100, 100], B=[300, 300], tok_off=[0, 100, 264]),       # second sequence overlaps
+])
+def test_invalid_layers_are_rejected(lib, kw):
+    L = _layer(**kw)
+    assert adakv.workspace_bytes(L) == 0
+    one = ctypes.c_void_p(16)      # never dereferenced: validation comes first
+    st = lib.adakv_score(ctypes.byref(L.c), one, one, None, one, one, 1 << 30, None)
+    assert st == -1
+    assert lib.adakv_allocate(ctypes.byref(L.c), one, one, one, one, 1 << 30, None) == -1
+    assert lib.adakv_select(ctypes.byref(L.c), one, one, one, one, one, 1 << 30, None) == -1
+    assert lib.adakv_compact(ctypes.byref(L.c), one, one, one, one, one, one, None) == -1
+
+
+@pytest.mark.parametrize("kw", [dict(d=96), dict(dtype=torch.float16), dict(k_strides=(8 * 128 + 4, 128))])
+def test_unsupported_layers(lib, kw):
+    L = _layer(**kw)
+    one = ctypes.c_void_p(16)
+    assert lib.adakv_score(ctypes.byref(L.c), one, one, None, one, one, 1 << 30, None) == -2
+
+
+def test_null_pointers_and_small_workspace(lib):
+    L = _layer()
+    one = ctypes.c_void_p(16)
+    assert lib.adakv_score(ctypes.byref(L.c), None, one, None, one, one, 1 << 30, None) == -1
+    assert lib.adakv_score(ctypes.byref(L.c), one, one, None, one, one, 8, None) == -3
+    assert lib.adakv_score(ctypes.byref(L.c), one, one, None, one, None, 1 << 30, None) == -3
+    assert lib.adakv_allocate(ctypes.byref(L.c), one, None, one, one, 1 << 30, None) == -1
+    assert lib.adakv_score(None, one, one, None, one, one, 1 << 30, None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libadakv.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load_library()
