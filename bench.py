@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the Ada-KV per-layer compression step on one MI355X.
+
+One step = one pass of the whole hot path (adakv_score + adakv_allocate + adakv_select +
+adakv_compact, one stream, no host synchronisation in between) over one seeded synthetic
+layer.  Inputs are resident in HBM before the timed region; the step rotates over several
+distinct input sets (more than a gigabyte in total, against 256 MB of memory-side cache) so
+that the K stream really comes from HBM.
+
+Prints ONE JSON line.  `value` is prefix tokens compressed per second (the layer's n divided
+by the time of a step).  `roofline` describes the dominant kernel, timed live with events
+recorded in front of and behind it on the launch stream (adakv_trace_arm) in a second pass
+over the same inputs; `cpu_baseline` is the fp64 CPU oracle on the same layer.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes(wl, kept_rows):
+    """Bytes the path has to move per layer call, per stage (one read of K for scoring, one
+    write and two reads of the scores, one read and one write of every kept K and V row)."""
+    esz = 2 if str(wl.dtype).endswith("bfloat16") else 4
+    n_tot = wl.total_prefix_tokens
+    k_stream = n_tot * wl.h_kv * wl.d * esz
+    sc = n_tot * wl.h_kv * 4
+    gather = kept_rows * wl.d * esz * 2 * 2
+    return {"score": k_stream + sc, "allocate": sc, "select": sc + kept_rows * 4,
+            "compact": gather + kept_rows * 4, "k_stream": k_stream}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama8b_128k",
+                    help="llama8b_128k (the headline), llama8b_32k, llama8b_ragged, llama70b_128k, tiny")
+    ap.add_argument("--alpha", type=float, default=None)
+    ap.add_argument("--sets", type=int, default=5, help="distinct input sets rotated over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); "
+                 "use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2407_11550_amd as adakv
+    from paper_2407_11550_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.workload(args.workload, alpha=args.alpha)
+    layer = adakv.Layer.from_workload(wl)
+    sets = [synth.generate(wl, layer=i, device=dev) for i in range(args.sets)]
+    ws = torch.empty(adakv.workspace_bytes(layer), dtype=torch.uint8, device=dev)
+    bufs = dict(scores=torch.empty(layer.num_scores, dtype=torch.float32, device=dev),
+                budgets=torch.empty(layer.num_segments, dtype=torch.int32, device=dev),
+                cu_seqlens=torch.empty(layer.num_segments + 1, dtype=torch.int32, device=dev),
+                indices=torch.empty(layer.num_rows_out, dtype=torch.int32, device=dev),
+                K_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev),
+                V_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev))
+
+    def step(i):
+        q, K, V = sets[i % len(sets)]
+        return adakv.compress(layer, q, K, V, ws=ws, bufs=bufs)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = 1000.0 * (t1 - t0) / args.steps
+    tokens = wl.total_prefix_tokens
+    value = tokens / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations, live, events on the launch stream (a second pass) ------------
+    per_kernel = {}
+    order = []
+    trace_steps = min(args.steps, 50)
+    for i in range(trace_steps):
+        with adakv.KernelTrace(64) as tr:
+            step(i)
+        torch.cuda.synchronize()
+        for name, us in tr.durations_us():
+            if name not in per_kernel:
+                per_kernel[name] = []
+                order.append(name)
+            per_kernel[name].append(us)
+    kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
+    kept = layer.num_rows_out
+    alg = algorithmic_bytes(wl, kept)
+    dominant = max(kernels, key=kernels.get)
+    # bytes one launch of the dominant kernel has to move: a scoring sweep reads K once
+    if dominant.startswith("score_") and dominant not in ("score_pool", "score_lse_combine"):
+        dom_bytes = alg["k_stream"]
+    elif dominant == "compact":
+        dom_bytes = alg["compact"]
+    else:
+        dom_bytes = tokens * wl.h_kv * 4
+    dom_us = kernels[dominant]
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    total_alg = alg["score"] + alg["allocate"] + alg["select"] + alg["compact"]
+    flops = 2.0 * wl.g * wl.w * wl.d * wl.h_kv * tokens
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
+
+    # ---- the oracle on the host cores, same layer (one full layer call) ---------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+
+        from oracle import adakv_oracle as O
+        q, K, V = sets[0]
+        b_n, b_B = wl.n[0], wl.B[0]
+        off = wl.tok_off
+        qd = q[0].double().cpu().numpy()
+        Kd = K[off[0]:off[1]].double().cpu().numpy()
+        Vd = V[off[0]:off[1]].float().cpu().numpy()
+        c0 = time.perf_counter()
+        O.compress_layer(qd, Kd, Vd, b_n, wl.w, wl.pool_k, b_B, wl.alpha)
+        c1 = time.perf_counter()
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        cpu = {"value": round(b_n / (c1 - c0), 1), "unit": "prefix tokens/s", "cores": threads,
+               "kind": "oracle", "seconds": round(c1 - c0, 3),
+               "sample": f"one full layer call (sequence 0 of {wl.name}: n={b_n}, all four steps), "
+                         f"fp64 numpy; BLAS threads={threads} for the logit matmuls, the rest single-threaded"}
+
+    out = {
+        "metric": "prefix tokens compressed/sec per layer (score+allocate+select+compact)",
+        "value": round(value, 1), "unit": "prefix tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if str(wl.dtype).endswith("bfloat16") else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "h_q": wl.h_q, "h_kv": wl.h_kv, "d": wl.d, "n": wl.n,
+                   "w": wl.w, "pool_k": wl.pool_k, "B": wl.B, "alpha": wl.alpha, "batch": wl.batch,
+                   "input_sets_rotated": len(sets)},
+        "pipeline_hbm_frac": round(total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "pipeline_algorithmic_bytes": total_alg,
+        "score_mfma_tflops": round(flops / (sum(v for k, v in kernels.items() if k.startswith("score_")) * 1e-6) / 1e12, 2),
+        "kernels_us": {k: round(kernels[k], 2) for k in order},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

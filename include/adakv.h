@@ -159,6 +159,24 @@ int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budge
 int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int32_t *indices,
                   const int32_t *cu_seqlens, void *K_out, void *V_out, void *hip_stream);
 
+/*
+ * Profiling aid for benchmarks (no part of the method).  While armed, on the arming host thread,
+ * the library records the caller's events, in order, on the call's stream: one in front of every
+ * kernel it launches and one at the end of every ABI call, until the array is used up.  Event i
+ * to event i+1 therefore brackets the kernel named adakv_trace_name(i); the name "end" marks the
+ * end of a call.  The extra stream markers slow the pipeline down a little, so throughput is
+ * measured unarmed.
+ *
+ *   events (host) array of n_events hipEvent_t handles created by the caller, which must stay
+ *          alive until adakv_trace_disarm; 1 <= n_events <= ADAKV_TRACE_MAX
+ * adakv_trace_disarm returns how many events were recorded; adakv_trace_name(i) is valid until
+ * the next adakv_trace_arm on the same thread.
+ */
+#define ADAKV_TRACE_MAX 256
+int adakv_trace_arm(void *const *events, int n_events);
+int adakv_trace_disarm(void);
+const char *adakv_trace_name(int i);
+
 #ifdef __cplusplus
 }
 #endif

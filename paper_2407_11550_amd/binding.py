@@ -65,6 +65,12 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = args
+    lib.adakv_trace_arm.restype = ctypes.c_int
+    lib.adakv_trace_arm.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
+    lib.adakv_trace_disarm.restype = ctypes.c_int
+    lib.adakv_trace_disarm.argtypes = []
+    lib.adakv_trace_name.restype = ctypes.c_char_p
+    lib.adakv_trace_name.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
 
@@ -212,3 +218,37 @@ def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, b
     idx = select(layer, sc, bud, cu, b.get("indices"), ws=ws, stream=stream)
     K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
     return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
+
+
+class KernelTrace:
+    """Per-kernel timing through adakv_trace_arm: inside the `with` block every kernel the
+    library launches (on torch's current stream) is bracketed by events."""
+
+    def __init__(self, capacity=128):
+        self.events = [torch.cuda.Event(enable_timing=True) for _ in range(capacity)]
+        for ev in self.events:                      # the first record creates the HIP event
+            ev.record()
+        self._arr = (ctypes.c_void_p * capacity)(*[ev.cuda_event for ev in self.events])
+        self.used = 0
+        self.names = []
+
+    def __enter__(self):
+        st = load_library().adakv_trace_arm(self._arr, len(self.events))
+        if st != 0:
+            raise AdaKVError(st, "adakv_trace_arm")
+        return self
+
+    def __exit__(self, *exc):
+        lib = load_library()
+        self.names = [lib.adakv_trace_name(i).decode() for i in range(len(self.events))]
+        self.used = lib.adakv_trace_disarm()
+        self.names = self.names[:self.used]
+        return False
+
+    def durations_us(self):
+        """[(kernel name, microseconds)] for every bracketed kernel; call after a synchronize."""
+        out = []
+        for i in range(self.used - 1):
+            if self.names[i] != "end":
+                out.append((self.names[i], 1000.0 * self.events[i].elapsed_time(self.events[i + 1])))
+        return out

@@ -67,6 +67,19 @@ static size_t workspace_for(const SeqTab &st, const Dims &dm, int dtype) {
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
+static thread_local struct {
+  void *const *events = nullptr;
+  int capacity = 0, used = 0;
+  const char *names[ADAKV_TRACE_MAX];
+} g_trace;
+
+void trace_mark(hipStream_t s, const char *name) {
+  if (!g_trace.events || g_trace.used >= g_trace.capacity) return;
+  g_trace.names[g_trace.used] = name;
+  (void)hipEventRecord((hipEvent_t)g_trace.events[g_trace.used], s);
+  g_trace.used += 1;
+}
+
 }  // namespace adakv
 
 using namespace adakv;
@@ -77,6 +90,25 @@ size_t adakv_workspace_bytes(const adakv_layer *L) {
   SeqTab st; Dims dm;
   if (build_tables(L, st, dm) != ADAKV_OK) return 0;
   return workspace_for(st, dm, L->dtype);
+}
+
+int adakv_trace_arm(void *const *events, int n_events) {
+  if (!events || n_events < 1 || n_events > ADAKV_TRACE_MAX) return ADAKV_EINVAL;
+  g_trace.events = events;
+  g_trace.capacity = n_events;
+  g_trace.used = 0;
+  return ADAKV_OK;
+}
+
+int adakv_trace_disarm(void) {
+  const int used = g_trace.used;
+  g_trace.events = nullptr;
+  g_trace.capacity = 0;
+  return used;
+}
+
+const char *adakv_trace_name(int i) {
+  return (i >= 0 && i < g_trace.used) ? g_trace.names[i] : "";
 }
 
 const char *adakv_strerror(int status) {
@@ -105,6 +137,7 @@ int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const
                      ? launch_score_mfma(st, dm, q_window, K, row_lse, scores, wsp, pl, s)
                      : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
                                             pl, s);
+  trace_mark(s, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -118,6 +151,7 @@ int adakv_allocate(const adakv_layer *L, const float *scores, int32_t *budgets,
   if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   hipError_t e = launch_allocate(st, dm, scores, budgets, cu_seqlens, wsp, (hipStream_t)hip_stream);
+  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -133,6 +167,7 @@ int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budge
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   hipError_t e = launch_select(st, dm, scores, budgets, cu_seqlens, indices, wsp,
                                (hipStream_t)hip_stream);
+  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -146,6 +181,7 @@ int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int3
     return ADAKV_EUNSUPPORTED;
   hipError_t e = launch_compact(st, dm, L->dtype, K, V, indices, cu_seqlens, K_out, V_out,
                                 (hipStream_t)hip_stream);
+  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 

@@ -84,4 +84,18 @@ hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const voi
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Profiling aid (adakv_trace_arm): while armed on this host thread, an event is recorded on the
+// stream in front of every kernel and at the end of every ABI call.
+void trace_mark(hipStream_t s, const char *name);
+void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float *part_m,
+                        const float *part_l, float *lse, hipStream_t s);
+void launch_pool(const SeqTab &st, const Dims &dm, const float *raw, float *scores,
+                 hipStream_t s);
+
+#define ADAKV_LAUNCH(name, kernel, grid, block, stream, ...)              \
+  do {                                                                    \
+    ::adakv::trace_mark(stream, name);                                    \
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);      \
+  } while (0)
+
 }  // namespace adakv

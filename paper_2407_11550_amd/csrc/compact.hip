@@ -44,7 +44,7 @@ hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const voi
   const int rpb = 256 / lpr;
   dim3 grid((rows + rpb - 1) / rpb), block(256);
 #define ADAKV_LAUNCH_COMPACT(LPR)                                                              \
-  hipLaunchKernelGGL(compact_kernel<LPR>, grid, block, 0, s, st, dm.h_kv, nseg,                \
+  ADAKV_LAUNCH("compact", compact_kernel<LPR>, grid, block, s, st, dm.h_kv, nseg,              \
                      dm.k_stride_tok * esz, dm.k_stride_head * esz, dm.v_stride_tok * esz,     \
                      dm.v_stride_head * esz, (const char *)K, (const char *)V, indices,        \
                      cu_seqlens, (char *)K_out, (char *)V_out, rows, dm.w)

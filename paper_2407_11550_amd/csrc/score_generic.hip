@@ -212,15 +212,15 @@ ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype) {
 
 void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float *part_m,
                         const float *part_l, float *lse, hipStream_t s) {
-  hipLaunchKernelGGL(lse_combine_kernel, dim3((RQ + 255) / 256, st.batch), dim3(256), 0, s, st, ct,
-                     RQ, part_m, part_l, lse);
+  ADAKV_LAUNCH("score_lse_combine", lse_combine_kernel, dim3((RQ + 255) / 256, st.batch),
+               dim3(256), s, st, ct, RQ, part_m, part_l, lse);
 }
 
 void launch_pool(const SeqTab &st, const Dims &dm, const float *raw, float *scores,
                  hipStream_t s) {
   const ChunkTab ct = make_chunks(st, GEN_CHUNK);
-  hipLaunchKernelGGL(pool_kernel, dim3(ct.off[st.batch], dm.h_kv), dim3(256), 0, s, st, ct,
-                     dm.pool_k, raw, scores);
+  ADAKV_LAUNCH("score_pool", pool_kernel, dim3(ct.off[st.batch], dm.h_kv), dim3(256), s, st, ct,
+               dm.pool_k, raw, scores);
 }
 
 template <typename T, int D>
@@ -233,13 +233,13 @@ static void run_generic(const SeqTab &st, const Dims &dm, const void *q, const v
   float *lse = (float *)(ws + pl.lse), *raw = (float *)(ws + pl.raw);
   const float *use_lse = row_lse;
   if (!row_lse) {
-    hipLaunchKernelGGL((stats_generic_kernel<T, D>), grid, block, 0, s, st, ct, dm, (const T *)q,
-                       (const T *)K, part_m, part_l);
+    ADAKV_LAUNCH("score_stats_fma", (stats_generic_kernel<T, D>), grid, block, s, st, ct, dm,
+                 (const T *)q, (const T *)K, part_m, part_l);
     launch_lse_combine(st, ct, dm.h_q * dm.w, part_m, part_l, lse, s);
     use_lse = lse;
   }
-  hipLaunchKernelGGL((raw_generic_kernel<T, D>), grid, block, 0, s, st, ct, dm, (const T *)q,
-                     (const T *)K, use_lse, raw);
+  ADAKV_LAUNCH("score_weights_fma", (raw_generic_kernel<T, D>), grid, block, s, st, ct, dm,
+               (const T *)q, (const T *)K, use_lse, raw);
   launch_pool(st, dm, raw, scores, s);
 }
 

@@ -391,13 +391,14 @@ static hipError_t run_passes(const SeqTab &st, const Dims &dm, const float *scor
   int zb = (int)((zero_words + 256 * 8 - 1) / (256 * 8));
   if (zb < 1) zb = 1;
   if (zb > 1024) zb = 1024;
-  hipLaunchKernelGGL(topk_init_kernel, dim3(zb), dim3(256), 0, s, st, h, LAYER, budgets_in,
+  ADAKV_LAUNCH(LAYER ? "alloc_init" : "select_init", topk_init_kernel, dim3(zb), dim3(256), s, st,
+               h, LAYER, budgets_in,
                      (unsigned *)ws, zero_words, prefix, krem);
   dim3 grid(ct.off[st.batch], h), block(256);
 #define ADAKV_PASS(P)                                                                          \
-  hipLaunchKernelGGL((topk_pass_kernel<P, LAYER>), grid, block, 0, s, st, ct, h, dm.w,         \
-                     dm.alpha_fix, scores, hist, ticket, gt, prefix, krem, thr, ties,          \
-                     budgets_out, cu)
+  ADAKV_LAUNCH(LAYER ? "alloc_pass" #P : "select_pass" #P, (topk_pass_kernel<P, LAYER>), grid,   \
+               block, s, st, ct, h, dm.w, dm.alpha_fix, scores, hist, ticket, gt, prefix, krem,  \
+               thr, ties, budgets_out, cu)
   ADAKV_PASS(0);
   ADAKV_PASS(1);
   ADAKV_PASS(2);
@@ -418,9 +419,9 @@ hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
   dim3 grid(ct.off[st.batch], dm.h_kv), block(256);
-  hipLaunchKernelGGL(emit_count_kernel, grid, block, 0, s, st, ct, dm.h_kv, scores,
+  ADAKV_LAUNCH("select_count", emit_count_kernel, grid, block, s, st, ct, dm.h_kv, scores,
                      (const unsigned *)(ws + p.thr), (int *)(ws + p.chunk_cnt));
-  hipLaunchKernelGGL(emit_write_kernel, grid, block, 0, s, st, ct, dm.h_kv, dm.w, scores,
+  ADAKV_LAUNCH("select_emit", emit_write_kernel, grid, block, s, st, ct, dm.h_kv, dm.w, scores,
                      (const unsigned *)(ws + p.thr), (const int *)(ws + p.ties),
                      (const int *)(ws + p.chunk_cnt), budgets, cu_seqlens, indices,
                      st.out_off[st.batch]);
