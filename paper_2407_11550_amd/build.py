@@ -10,6 +10,8 @@ SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "select.hip", "comp
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA accumulators straight in VGPRs: no accvgpr moves in front of the softmax math
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-unused-function"]
 
 

@@ -9,20 +9,24 @@
 // Sweep 2 walks the key chunks in the opposite order, so it starts on what sweep 1 left in the
 // memory-side cache.  A caller-supplied row_lse skips sweep 1.
 //
-// Work split.  A workgroup (4 wavefronts) owns CHUNK consecutive keys of one KV head; all g
-// query heads of the group share every K tile.  A wavefront keeps up to 128 window rows of Q in
-// registers as MFMA operands for the whole chunk (MB blocks of 32 rows); RS wavefronts split
-// the rows when the head has more than 128, and the 4/RS groups of wavefronts take the 32-key
-// tiles of the chunk in turn.  A K tile travels HBM -> registers (coalesced 16-byte loads, whole
-// 256-byte rows) -> the wavefront's own LDS slot (padded rows) -> registers in operand layout.
+// Work split.  A workgroup owns CHUNK consecutive keys of one KV head; all g query heads of the
+// group share every K tile.  A wavefront keeps at most 64 window rows of Q in registers as MFMA
+// operands for the whole chunk (MB blocks of 32 rows), which leaves room for two wavefronts per
+// SIMD, so one wavefront's exponentials overlap the other's matrix work.  RS wavefronts split
+// the rows of a head, and the KG = NW/RS groups of wavefronts take the 32-key tiles of the
+// chunk in turn.  A K tile travels HBM -> registers (coalesced 16-byte loads of whole rows) ->
+// the wavefront's own LDS slot (padded rows) -> registers in operand layout.
 //
 // Operand roles differ between the sweeps because of what the accumulator layout makes cheap
 // (D[i][j]: lane = column j, 16 rows i per lane):
 //   sweep 1: D = K_tile Q^T, a lane owns ONE window row and 16 keys: running (max, sum) per
 //            lane, nothing crosses lanes until the chunk is done;
 //   sweep 2: D = Q K_tile^T, a lane owns ONE key and 16 window rows: the sum over rows is
-//            lane-local adds plus one cross-half add.
+//            lane-local adds plus one cross-half add; partial sums of the RS row groups meet
+//            in LDS when the chunk is done and are added in a fixed order.
 #include <math.h>
+
+#include <type_traits>
 
 #include "common.h"
 
@@ -32,182 +36,227 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int MFMA_CHUNK = 2048;   // keys per workgroup
 constexpr int TILE = 32;           // keys per MFMA tile
-
-union Frag {
-  uint4 u;
-  bf16x8 v;
-};
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ bf16x8 as_bf16(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-template <int D, int MB, int RS, int PASS>
-__global__ __launch_bounds__(256) void score_mfma_kernel(
+template <int D, int MB, int RS, int KG, int CHUNK, int PASS>
+__global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     SeqTab st, ChunkTab ct, Dims dm, float c_log2, const unsigned short *__restrict__ q,
     const unsigned short *__restrict__ K, const float *__restrict__ lse,
-    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ raw) {
+    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ out, int halo) {
+  constexpr int NW = RS * KG;                // wavefronts per workgroup
+  constexpr int NT = 64 * NW;
   constexpr int KS = D / 16;                 // MFMA k-steps per tile
   constexpr int ROW16 = D * 2 / 16;          // 16-byte words per K row
   constexpr int STRIDE16 = ROW16 + 1;        // padded LDS row, in 16-byte words
-  constexpr int LPR = ROW16;                 // lanes that load one row
-  constexpr int RPI = 64 / LPR;              // rows per load instruction
+  constexpr int RPI = 64 / ROW16;            // rows per load instruction
   constexpr int NLD = TILE / RPI;            // load instructions per tile
-  constexpr int KG = 4 / RS;                 // wavefront groups that take different tiles
   constexpr int RW = 32 * MB;                // window rows per wavefront
+  constexpr int RPAD = RW * RS;              // window rows per workgroup (padded)
 
-  __shared__ uint4 kt[4][TILE * STRIDE16];   // one K tile slot per wavefront
-  __shared__ float sh_a[4][RW];              // sweep 1: per-wave row max; sweep 2: partial sums
-  __shared__ float sh_b[4][RW];              // sweep 1: per-wave row sum
+  __shared__ u32x4 kt[NW][TILE * STRIDE16];  // one K tile slot per wavefront
+  __shared__ float sh_rows[2][NW][RW];       // sweep 1: per-wave row (max, sum); sweep 2: [0][0] lse
+  constexpr int HALO = TILE;                 // keys scored on either side of the chunk for the pool
+  __shared__ float sh_part[PASS == 2 ? RS : 1][PASS == 2 ? CHUNK + 2 * HALO : 1];
+  __shared__ float sh_cm[PASS == 2 ? NT : 1], sh_cl[PASS == 2 ? NT : 1];
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // the wavefront index is the same in all lanes: telling the compiler keeps everything derived
+  // from it (tile numbers, K addresses, loop conditions) in scalar registers
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int half = lane >> 5, l32 = lane & 31;
   const int kg = wv / RS, rs = wv % RS;
   const int h = dm.h_kv;
-  const int total_chunks = ct.off[st.batch];
   const int c = blockIdx.x % h;
   int cg = blockIdx.x / h;
-  if (PASS == 2) cg = total_chunks - 1 - cg;
+  if (PASS == 2) cg = ct.off[st.batch] - 1 - cg;
   const int b = find_seq(ct, st.batch, cg);
   const int chunk = cg - ct.off[b];
   const int n = st.n[b];
   const int R = dm.g * dm.w, RQ = dm.h_q * dm.w;
-  const int k0 = chunk * MFMA_CHUNK;
-  const int k1 = min(n, k0 + MFMA_CHUNK);
+  const int kc0 = chunk * CHUNK;             // first key of the chunk
+  const int kc1 = min(n, kc0 + CHUNK);
+  // sweep 2 with the pool fused also scores one tile of neighbours on each side
+  const int k0 = (PASS == 2 && halo && kc0 > 0) ? kc0 - HALO : kc0;
+  const int k1 = (PASS == 2 && halo) ? min(n, kc1 + HALO) : kc1;
   const int ntiles = (k1 - k0 + TILE - 1) / TILE;
   const int row0 = rs * RW;                  // first window row of this wavefront
+  const size_t head_row0 = (size_t)b * RQ + (size_t)c * R;
 
   // ---- window queries of this wavefront as MFMA operands, kept for the whole chunk ----------
-  Frag qf[MB][KS];
-  {
-    const unsigned short *qhead = q + ((size_t)b * RQ + (size_t)c * R) * D;
+  // (rows past R are loaded from row R-1 and zeroed, so every load is unconditional)
+  bf16x8 qf[MB][KS];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      const int row = row0 + mb * 32 + l32;
+  for (int mb = 0; mb < MB; ++mb) {
+    const int row = row0 + mb * 32 + l32;
+    const unsigned keep = row < R ? 0xFFFFFFFFu : 0u;
+    const unsigned short *src = q + (head_row0 + min(row, R - 1)) * D + half * 8;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        if (row < R)
-          qf[mb][s].u = *reinterpret_cast<const uint4 *>(qhead + (size_t)row * D + s * 16 + half * 8);
-        else
-          qf[mb][s].u = make_uint4(0u, 0u, 0u, 0u);
-      }
+    for (int s = 0; s < KS; ++s) {
+      u32x4 v = *reinterpret_cast<const u32x4 *>(src + s * 16);
+      v &= keep;
+      qf[mb][s] = as_bf16(v);
     }
   }
 
-  // sweep 2: log2-domain log-sum-exp of the 16 rows a lane sees in each row block
+  // sweep 2: log2-domain log-sum-exp of the 16 rows a lane sees in each row block; +inf on the
+  // padding rows makes their weights exactly zero
   float l2[PASS == 2 ? MB : 1][16];
   if (PASS == 2) {
+    float *sh_lse = &sh_rows[0][0][0];       // RPAD floats
+    if (lse) {
+      for (int i = tid; i < RPAD; i += NT) sh_lse[i] = (i < R) ? lse[head_row0 + i] * LOG2E : INFINITY;
+    } else {
+      // combine sweep 1's partial (max, sum) of this head's rows over the sequence's chunks:
+      // NT/RPAD threads share a row, each takes every (NT/RPAD)-th chunk, LDS joins them
+      constexpr int SL = NT / RPAD;
+      const int qi = tid % RPAD, sl = tid / RPAD;
+      float M = -INFINITY, L = 0.0f;
+      if (qi < R) {
+        for (int k = ct.off[b] + sl; k < ct.off[b + 1]; k += SL) {
+          const size_t o = (size_t)k * RQ + (size_t)c * R + qi;
+          const float m = part_m[o] * LOG2E, l = part_l[o];
+          const float nm = fmaxf(M, m);
+          const float ref = (nm == -INFINITY) ? 0.0f : nm;
+          L = L * fast_exp2(M - ref) + l * fast_exp2(m - ref);
+          M = nm;
+        }
+      }
+      sh_cm[tid] = M;
+      sh_cl[tid] = L;
+      __syncthreads();
+      if (tid < RPAD) {
+        float Mt = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < SL; ++i) Mt = fmaxf(Mt, sh_cm[i * RPAD + tid]);
+        const float ref = (Mt == -INFINITY) ? 0.0f : Mt;
+        float Lt = 0.0f;
+#pragma unroll
+        for (int i = 0; i < SL; ++i) Lt += sh_cl[i * RPAD + tid] * fast_exp2(sh_cm[i * RPAD + tid] - ref);
+        sh_lse[tid] = (tid < R) ? Mt + __builtin_amdgcn_logf(Lt) : INFINITY;
+      }
+    }
+    __syncthreads();
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row0 + mb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-        l2[mb][r] = (row < R) ? lse[(size_t)b * RQ + (size_t)c * R + row] * 1.4426950408889634f
-                              : INFINITY;
-      }
+      for (int r = 0; r < 16; ++r)
+        l2[mb][r] = sh_lse[row0 + mb * 32 + 8 * (r / 4) + 4 * half + (r % 4)];
   }
   // sweep 1: running statistics of the window row this lane owns in each row block
   float rm[MB], rl[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) { rm[mb] = -INFINITY; rl[mb] = 0.0f; }
 
+  // K addressing: a wave-uniform 64-bit base per tile (scalar registers) plus a 32-bit per-lane
+  // offset, so the vector ALU does no address arithmetic inside the loop.
   const char *kbase = reinterpret_cast<const char *>(K) +
                       ((size_t)st.tok_off[b] * dm.k_stride_tok + (size_t)c * dm.k_stride_head) * 2;
   const size_t tok_bytes = (size_t)dm.k_stride_tok * 2;
-  const int ld_row = lane / LPR, ld_col = lane % LPR;
-  uint4 *slot = kt[wv];
+  const int ld_row = lane / ROW16, ld_col = lane % ROW16;
+  const unsigned lane_off = (unsigned)ld_row * (unsigned)tok_bytes + (unsigned)ld_col * 16u;
+  u32x4 *slot = kt[wv];
+  const int wr_off = ld_row * STRIDE16 + ld_col;
+  const int rd_off = l32 * STRIDE16 + half;
 
-  uint4 g[NLD];
-  auto load_tile = [&](int tile) {
-    const int base = k0 + tile * TILE;
+  u32x4 g[NLD];
+  // full tile: all 32 rows exist
+  auto load_full = [&](int tile) {
+    const char *tb = kbase + (size_t)(k0 + tile * TILE) * tok_bytes;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i)
+      g[i] = *reinterpret_cast<const u32x4 *>(tb + (size_t)(i * RPI) * tok_bytes + lane_off);
+  };
+  // last tile of a sequence: rows past the end re-read row n-1 (masked out later)
+  auto load_ragged = [&](int tile) {
+    const int base_ = k0 + tile * TILE + ld_row;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int key = min(base + i * RPI + ld_row, n - 1);   // rows past the end re-read the last
-      g[i] = *reinterpret_cast<const uint4 *>(kbase + (size_t)key * tok_bytes + ld_col * 16);
+      const int key_ = min(base_ + i * RPI, n - 1);
+      g[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key_ * tok_bytes + ld_col * 16);
     }
   };
+  auto load_tile = [&](int tile) {
+    if (k0 + tile * TILE + TILE <= n) load_full(tile); else load_ragged(tile);
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) slot[wr_off + i * RPI * STRIDE16] = g[i];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
 
-  const int iters = (ntiles + KG - 1) / KG;
-  if (kg < ntiles) load_tile(kg);
-  for (int it = 0; it < iters; ++it) {
-    const int tile = it * KG + kg;
-    const bool active = tile < ntiles;
-    Frag kf[KS];
-    if (active) {
-      // registers -> LDS slot -> operand layout (same wavefront writes and reads)
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) slot[(i * RPI + ld_row) * STRIDE16 + ld_col] = g[i];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-      for (int s = 0; s < KS; ++s) kf[s].u = slot[l32 * STRIDE16 + s * 2 + half];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      if (tile + KG < ntiles) load_tile(tile + KG);           // next tile's loads fly during the math
-    }
+  // one 32-key tile against this wavefront's rows; RAGGED masks keys at or past n
+  auto compute = [&](auto ragged_tag, const bf16x8 (&kf)[KS], int tile) {
+    constexpr bool RAGGED = decltype(ragged_tag)::value;
     const int base = k0 + tile * TILE;
-    const bool ragged = base + TILE > n;
-
     if (PASS == 1) {
-      if (active) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          floatx16 acc = {0};
+      for (int mb = 0; mb < MB; ++mb) {
+        floatx16 acc = {0};
 #pragma unroll
-          for (int s = 0; s < KS; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[mb][s].v, acc, 0, 0, 0);
-          // acc[r]: key base + 8*(r/4) + 4*half + r%4, window row row0 + mb*32 + l32
-          if (ragged) {
+        for (int s = 0; s < KS; ++s)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[mb][s], acc, 0, 0, 0);
+        // acc[r]: key base + 8*(r/4) + 4*half + r%4, window row row0 + mb*32 + l32
+        if (RAGGED) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if (base + 8 * (r / 4) + 4 * half + (r % 4) >= n) acc[r] = -INFINITY;
-          }
-          float tm = acc[0];
-#pragma unroll
-          for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[r]);
-          const float nm = fmaxf(rm[mb], tm * c_log2);
-          const float ref = (nm == -INFINITY) ? 0.0f : nm;
-          float sum = 0.0f;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c_log2, -ref));
-          rl[mb] = rl[mb] * fast_exp2(rm[mb] - ref) + sum;
-          rm[mb] = nm;
+          for (int r = 0; r < 16; ++r)
+            if (base + 8 * (r / 4) + 4 * half + (r % 4) >= n) acc[r] = -INFINITY;
         }
+        float tm = acc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[r]);
+        const float nm = fmaxf(rm[mb], tm * c_log2);
+        const float ref = (nm == -INFINITY) ? 0.0f : nm;
+        float sum = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c_log2, -ref));
+        rl[mb] = rl[mb] * fast_exp2(rm[mb] - ref) + sum;
+        rm[mb] = nm;
       }
     } else {
       float sum = 0.0f;
-      if (active) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          floatx16 acc = {0};
+      for (int mb = 0; mb < MB; ++mb) {
+        floatx16 acc = {0};
 #pragma unroll
-          for (int s = 0; s < KS; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mb][s].v, kf[s].v, acc, 0, 0, 0);
-          // acc[r]: window row row0 + mb*32 + 8*(r/4) + 4*half + r%4, key base + l32
+        for (int s = 0; s < KS; ++s)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mb][s], kf[s], acc, 0, 0, 0);
+        // acc[r]: window row row0 + mb*32 + 8*(r/4) + 4*half + r%4, key base + l32
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c_log2, -l2[mb][r]));
-        }
-        sum += __shfl_xor(sum, 32);
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c_log2, -l2[mb][r]));
       }
-      const int key = base + l32;
-      if (RS == 1) {
-        if (active && half == 0 && key < n)
-          raw[st.score_off[b] + (size_t)c * n + key] = sum * (1.0f / (float)R);
-      } else {
-        // the RS wavefronts of a group hold partial sums over their own rows: add in fixed order
-        if (active && half == 0) sh_a[wv][l32] = sum;
-        __syncthreads();
-        if (active && rs == 0 && half == 0 && key < n) {
-          float tot = 0.0f;
-#pragma unroll
-          for (int i = 0; i < RS; ++i) tot += sh_a[kg * RS + i][l32];
-          raw[st.score_off[b] + (size_t)c * n + key] = tot * (1.0f / (float)R);
-        }
-        __syncthreads();
-      }
+      sum += __shfl_xor(sum, 32);
+      // keys past n in a ragged tile get a value nobody reads
+      if (half == 0) sh_part[rs][tile * TILE + l32] = sum;   // key k0 + tile*TILE + l32
     }
+  };
+
+  // this wavefront's tiles: kg, kg + KG, ...  The next tile's loads fly during the math.
+  int tile = kg;
+  if (tile < ntiles) {
+    load_tile(tile);
+    store_tile();
+  }
+  while (tile < ntiles) {
+    // LDS slot -> operand layout (the same wavefront wrote it; LDS operations of one wavefront
+    // complete in order)
+    bf16x8 kf[KS];
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kf[s] = as_bf16(slot[rd_off + s * 2]);
+    const int next = tile + KG;
+    if (next < ntiles) load_tile(next);
+    if (k0 + tile * TILE + TILE <= n) compute(std::false_type{}, kf, tile);
+    else compute(std::true_type{}, kf, tile);
+    if (next < ntiles) store_tile();
+    tile = next;
   }
 
   if (PASS == 1) {
@@ -218,47 +267,80 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
       const float M = fmaxf(rm[mb], m2);
       const float ref = (M == -INFINITY) ? 0.0f : M;
       const float L = rl[mb] * fast_exp2(rm[mb] - ref) + s2 * fast_exp2(m2 - ref);
-      if (half == 0) { sh_a[wv][mb * 32 + l32] = M; sh_b[wv][mb * 32 + l32] = L; }
+      if (half == 0) { sh_rows[0][wv][mb * 32 + l32] = M; sh_rows[1][wv][mb * 32 + l32] = L; }
     }
     __syncthreads();
-    for (int qi = tid; qi < RW * RS; qi += 256) {
+    for (int qi = tid; qi < RPAD; qi += NT) {
       const int rsi = qi / RW, wi = qi % RW;
       float M = -INFINITY;
 #pragma unroll
-      for (int k = 0; k < KG; ++k) M = fmaxf(M, sh_a[k * RS + rsi][wi]);
+      for (int k = 0; k < KG; ++k) M = fmaxf(M, sh_rows[0][k * RS + rsi][wi]);
       const float ref = (M == -INFINITY) ? 0.0f : M;
       float L = 0.0f;
 #pragma unroll
-      for (int k = 0; k < KG; ++k) L += sh_b[k * RS + rsi][wi] * fast_exp2(sh_a[k * RS + rsi][wi] - ref);
+      for (int k = 0; k < KG; ++k)
+        L += sh_rows[1][k * RS + rsi][wi] * fast_exp2(sh_rows[0][k * RS + rsi][wi] - ref);
       if (qi < R) {
         const size_t o = (size_t)cg * RQ + (size_t)c * R + qi;
-        part_m[o] = M * 0.6931471805599453f;      // back to the natural-log domain
+        part_m[o] = M * LN2;                       // back to the natural-log domain
         part_l[o] = L;
       }
+    }
+  } else {
+    __syncthreads();
+    // add the RS row groups in a fixed order, take the mean, then (halo != 0) the max-pool:
+    // stride 1, same length, window clipped to the sequence (Section 4.1: kernel 7)
+    const float inv = 1.0f / (float)R;
+    const int span = k1 - k0;
+    for (int j = tid; j < span; j += NT) {
+      float tot = 0.0f;
+#pragma unroll
+      for (int i = 0; i < RS; ++i) tot += sh_part[i][j];
+      sh_part[0][j] = tot * inv;
+    }
+    __syncthreads();
+    float *dst = out + st.score_off[b] + (size_t)c * n;
+    const int r = halo ? dm.pool_k / 2 : 0;
+    for (int key = kc0 + tid; key < kc1; key += NT) {
+      const int lo = max(key - r, 0), hi = min(key + r, n - 1);
+      float m = sh_part[0][lo - k0];
+      for (int t = lo + 1; t <= hi; ++t) m = fmaxf(m, sh_part[0][t - k0]);
+      dst[key] = m;
     }
   }
 }
 
-template <int D, int MB, int RS>
+template <int D, int MB, int RS, int KG, int CHUNK>
 void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
               const float *row_lse, float *scores, char *ws, const ScorePlan &pl, hipStream_t s) {
-  const ChunkTab ct = make_chunks(st, MFMA_CHUNK);
+  const ChunkTab ct = make_chunks(st, CHUNK);
   const int nblk = ct.off[st.batch] * dm.h_kv;
-  const float c_log2 = dm.scale * 1.4426950408889634f;
+  const float c_log2 = dm.scale * LOG2E;
   float *part_m = (float *)(ws + pl.part_m), *part_l = (float *)(ws + pl.part_l);
   float *lse = (float *)(ws + pl.lse), *raw = (float *)(ws + pl.raw);
+  const dim3 block(64 * RS * KG);
+  // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a sequence has so
+  // many chunks that every workgroup re-reading them would cost more than a kernel, and it
+  // applies the max-pool itself when the pool radius fits into the one-tile halo.
+  int max_chunks = 0;
+  for (int b = 0; b < st.batch; ++b) max_chunks = ct.off[b + 1] - ct.off[b] > max_chunks ? ct.off[b + 1] - ct.off[b] : max_chunks;
+  const bool fuse_lse = max_chunks <= 128;
+  const bool fuse_pool = dm.pool_k / 2 <= TILE;
   const float *use_lse = row_lse;
   if (!row_lse) {
-    ADAKV_LAUNCH("score_stats_mfma", (score_mfma_kernel<D, MB, RS, 1>), dim3(nblk), dim3(256), s,
-                 st, ct, dm, c_log2, (const unsigned short *)q, (const unsigned short *)K,
-                 (const float *)nullptr, part_m, part_l, (float *)nullptr);
-    launch_lse_combine(st, ct, dm.h_q * dm.w, part_m, part_l, lse, s);
-    use_lse = lse;
+    ADAKV_LAUNCH("score_stats_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 1>), dim3(nblk),
+                 block, s, st, ct, dm, c_log2, (const unsigned short *)q,
+                 (const unsigned short *)K, (const float *)nullptr, part_m, part_l,
+                 (float *)nullptr, 0);
+    if (!fuse_lse) {
+      launch_lse_combine(st, ct, dm.h_q * dm.w, part_m, part_l, lse, s);
+      use_lse = lse;
+    }
   }
-  ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, 2>), dim3(nblk), dim3(256), s,
-               st, ct, dm, c_log2, (const unsigned short *)q, (const unsigned short *)K, use_lse,
-               (float *)nullptr, (float *)nullptr, raw);
-  launch_pool(st, dm, raw, scores, s);
+  ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 2>), dim3(nblk),
+               block, s, st, ct, dm, c_log2, (const unsigned short *)q, (const unsigned short *)K,
+               use_lse, part_m, part_l, fuse_pool ? scores : raw, fuse_pool ? 1 : 0);
+  if (!fuse_pool) launch_pool(st, dm, raw, scores, s);
 }
 
 template <int D>
@@ -266,11 +348,11 @@ void run_mfma_d(const SeqTab &st, const Dims &dm, const void *q, const void *K,
                 const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
                 hipStream_t s) {
   const int R = dm.g * dm.w;
-  if (R <= 32) run_mfma<D, 1, 1>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else if (R <= 64) run_mfma<D, 2, 1>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else if (R <= 128) run_mfma<D, 4, 1>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else if (R <= 256) run_mfma<D, 4, 2>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else run_mfma<D, 4, 4>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  if (R <= 32) run_mfma<D, 1, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else if (R <= 64) run_mfma<D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else if (R <= 128) run_mfma<D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else if (R <= 256) run_mfma<D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else run_mfma<D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
 }
 
 }  // namespace

@@ -128,21 +128,27 @@ __global__ __launch_bounds__(256) void topk_pass_kernel(
     }
   }
   __syncthreads();
+  // Publish the block's counts and take a ticket WITHOUT a device-scope fence (on this part a
+  // release fence writes the whole L2 back, which costs more than the pass itself).  Everything
+  // other blocks read is written by device-scope atomics, which execute at the point of
+  // coherence; a returning atomic has been performed there once its value is back, so waiting
+  // for the returned values orders the counts in front of the ticket.
   unsigned *gh = hist + ((size_t)P * nsegs + seg_head) * RADIX_BINS;
+  unsigned seen = 0u;
   for (int i = tid; i < NB; i += 256) {
     const unsigned v = lh[i];
-    if (v) atomicAdd(&gh[i], v);
+    if (v) seen |= __hip_atomic_fetch_add(&gh[i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  __threadfence();
+  asm volatile("" ::"v"(seen));          // the returned values are needed here: waits for them
   __syncthreads();
   if (tid == 0) {
     const unsigned nblk = (unsigned)(ct.off[b + 1] - ct.off[b]) * (LAYER ? (unsigned)h : 1u);
-    const unsigned t = atomicAdd(&ticket[(size_t)P * nsegs + S], 1u);
+    const unsigned t = __hip_atomic_fetch_add(&ticket[(size_t)P * nsegs + S], 1u, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
     sh_misc[0] = (t == nblk - 1u) ? 1u : 0u;
   }
   __syncthreads();
   if (sh_misc[0] == 0u) return;
-  __threadfence();
 
   // ---- last block of this segment: choose the digit that holds the krem-th largest --------
   const int c0 = LAYER ? 0 : c, c1 = LAYER ? h : c + 1;
