@@ -8,8 +8,13 @@
 //
 // A score becomes a 32-bit key whose unsigned order is the float order.  Three passes over the
 // scores take the key's bits 31..21, 20..10, 9..0; each pass histograms the digit of the
-// elements that still match the digits chosen so far, and the last block to finish a segment
-// picks the digit that holds the k-th largest element.
+// elements that still match the digits chosen so far.
+//
+// Blocks of one kernel never talk to each other: integer atomics add the per-block counts into
+// global histograms, and the digit that holds the k-th largest element is found by the NEXT
+// kernel, whose every block scans the (small) finished histogram in its prologue.  A kernel
+// boundary is the cheapest device-wide synchronisation on this part: a device-scope fence
+// inside a kernel writes a whole L2 back.
 #include "common.h"
 
 namespace adakv {
@@ -17,14 +22,10 @@ namespace adakv {
 namespace {
 
 struct TopkWs {             // byte offsets inside the workspace
-  size_t hist;              // u32 [3][batch*h][RADIX_BINS]
-  size_t ticket;            // u32 [3][batch*h]
-  size_t gt;                // i32 [batch*h]   elements strictly above the threshold, per head
+  size_t hist;              // u32 [3][batch*h][RADIX_BINS]  per-head digit counts
+  size_t hist_tot;          // u32 [3][batch][RADIX_BINS]    the same summed over heads (layer scope)
   size_t zero_end;          // everything before this is cleared by the init kernel
-  size_t prefix;            // u32 [batch*h]   digits chosen so far (scope segment index)
-  size_t krem;              // i32 [batch*h]   rank of the threshold among matching elements
-  size_t thr;               // u32 [batch*h]   final threshold key per head (head scope)
-  size_t ties;              // i32 [batch*h]   how many threshold-valued elements to take
+  size_t state;             // uint2 [2][batch*h]: (digits chosen, rank left) after passes 0 and 1
   size_t chunk_cnt;         // i32 [chunks][h][2]
   size_t total;
 };
@@ -34,13 +35,9 @@ TopkWs plan(const SeqTab &st, const Dims &dm) {
   const size_t nseg = (size_t)st.batch * dm.h_kv;
   size_t o = 0;
   p.hist = o; o += 3 * nseg * RADIX_BINS * 4;
-  p.ticket = o; o += align_up(3 * nseg * 4, 256);
-  p.gt = o; o += align_up(nseg * 4, 256);
+  p.hist_tot = o; o += 3 * (size_t)st.batch * RADIX_BINS * 4;
   p.zero_end = o;
-  p.prefix = o; o += align_up(nseg * 4, 256);
-  p.krem = o; o += align_up(nseg * 4, 256);
-  p.thr = o; o += align_up(nseg * 4, 256);
-  p.ties = o; o += align_up(nseg * 4, 256);
+  p.state = o; o += align_up(2 * nseg * 8, 256);
   p.chunk_cnt = o;
   o += align_up((size_t)make_chunks(st, SEL_CHUNK).off[st.batch] * dm.h_kv * 2 * 4, 256);
   p.total = o;
@@ -70,201 +67,242 @@ template <int P> __device__ __forceinline__ unsigned with_digit(unsigned prefix,
   return (prefix & 0xFFFFFC00u) | dgt;
 }
 
-__device__ __forceinline__ unsigned ld_u32(const unsigned *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ int ld_i32(const int *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+struct Rank {
+  unsigned prefix;   // digits chosen so far, in key position
+  int krem;          // rank of the threshold among the elements matching them; 0 = select nothing
+};
+
+// All 256 threads of a block: given the finished histogram of pass P (NB bins) and the rank
+// krem >= 1 among the elements it counts, find the digit whose bin holds that rank, counting
+// from the largest digit down.  Returns the digit and the rank inside its bin (>= 1).
+template <int NB>
+__device__ __forceinline__ void locate(const unsigned *__restrict__ bins, int krem,
+                                       unsigned &digit, int &rank_in_bin, unsigned *sh /*[8]*/) {
+  constexpr int PER = NB / 256;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  unsigned mine[PER];
+  unsigned s = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { mine[i] = bins[tid * PER + i]; s += mine[i]; }
+  unsigned suf = s;                                    // sum over lanes >= this one
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned v = __shfl_down(suf, off);
+    if (lane + off < 64) suf += v;
+  }
+  __syncthreads();                                     // sh may be in use by the caller
+  if (lane == 0) sh[wv] = suf;
+  if (tid == 0) { sh[4] = 0u; sh[5] = (unsigned)krem; }   // fallback keeps later reads in bounds
+  __syncthreads();
+  unsigned above = suf - s;                            // elements in bins owned by higher threads
+  for (int i = wv + 1; i < 4; ++i) above += sh[i];
+  if (above < (unsigned)krem && (unsigned)krem <= above + s) {
+    unsigned acc = above;
+#pragma unroll
+    for (int i = PER - 1; i >= 0; --i) {
+      if (acc < (unsigned)krem && (unsigned)krem <= acc + mine[i]) {
+        sh[4] = (unsigned)(tid * PER + i);
+        sh[5] = (unsigned)krem - acc;
+      }
+      acc += mine[i];
+    }
+  }
+  __syncthreads();
+  digit = sh[4];
+  rank_in_bin = (int)sh[5];
 }
 
-__global__ __launch_bounds__(256) void topk_init_kernel(SeqTab st, int h, bool layer_scope,
-                                                        const int *__restrict__ budgets,
-                                                        unsigned *__restrict__ zero_begin,
-                                                        size_t zero_words,
-                                                        unsigned *__restrict__ prefix,
-                                                        int *__restrict__ krem) {
+__global__ __launch_bounds__(256) void topk_init_kernel(unsigned *__restrict__ zero_begin,
+                                                        size_t zero_words) {
   const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   for (size_t i = i0; i < zero_words; i += (size_t)gridDim.x * blockDim.x) zero_begin[i] = 0u;
-  const int nseg = layer_scope ? st.batch : st.batch * h;
-  if (i0 < (size_t)nseg) {
-    prefix[i0] = 0u;
-    krem[i0] = layer_scope ? st.Bp[i0] : budgets[i0];
-  }
 }
 
-// One pass of the radix select.  grid.x runs over the SEL_CHUNK-sized chunks of all sequences,
-// grid.y over heads.  LAYER: the k-th largest is sought over all heads of a sequence.
+// Rank state in front of pass P for scope segment S: pass 0 starts from k; later passes take the
+// stored state of the pass before the previous one and scan the previous pass's histogram.
 template <int P, bool LAYER>
-__global__ __launch_bounds__(256) void topk_pass_kernel(
-    SeqTab st, ChunkTab ct, int h, int w, int alpha_fix, const float *__restrict__ scores,
-    unsigned *__restrict__ hist, unsigned *__restrict__ ticket, int *__restrict__ gt,
-    unsigned *__restrict__ prefix_g, int *__restrict__ krem_g, unsigned *__restrict__ thr_g,
-    int *__restrict__ ties_g, int *__restrict__ budgets, int *__restrict__ cu) {
+__device__ __forceinline__ Rank rank_before_pass(const SeqTab &st, int h, int b, int c,
+                                                 const int *__restrict__ budgets,
+                                                 const unsigned *__restrict__ hist,
+                                                 const unsigned *__restrict__ hist_tot,
+                                                 const uint2 *__restrict__ state, unsigned *sh) {
+  const int nsegs = st.batch * h;
+  const int S = LAYER ? b : b * h + c;
+  Rank r;
+  if (P <= 1) {
+    r.prefix = 0u;
+    r.krem = LAYER ? st.Bp[b] : budgets[b * h + c];
+  } else {
+    const uint2 v = state[(size_t)(P - 2) * nsegs + S];
+    r.prefix = v.x;
+    r.krem = (int)v.y;
+  }
+  if (P == 0 || r.krem <= 0) return r;
+  constexpr int Q = P - 1;                             // the pass whose histogram is scanned
+  constexpr int NBQ = (Q == 2) ? 1024 : RADIX_BINS;
+  const unsigned *bins = LAYER ? hist_tot + ((size_t)Q * st.batch + b) * RADIX_BINS
+                               : hist + ((size_t)Q * nsegs + b * h + c) * RADIX_BINS;
+  unsigned digit;
+  int rank;
+  locate<NBQ>(bins, r.krem, digit, rank, sh);
+  r.prefix = with_digit<Q>(r.prefix, digit);
+  r.krem = rank;
+  return r;
+}
+
+// One histogram pass.  grid.x runs over the SEL_CHUNK-sized chunks of all sequences, grid.y over
+// heads.  LAYER: the k-th largest is sought over all heads of a sequence.
+template <int P, bool LAYER>
+__global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, int h,
+                                                        const float *__restrict__ scores,
+                                                        const int *__restrict__ budgets,
+                                                        unsigned *__restrict__ hist,
+                                                        unsigned *__restrict__ hist_tot,
+                                                        uint2 *__restrict__ state) {
   constexpr int NB = (P == 2) ? 1024 : RADIX_BINS;
   __shared__ unsigned lh[RADIX_BINS];
-  __shared__ unsigned sh_scan[256];
-  __shared__ int sh_gt[64];
-  __shared__ unsigned sh_misc[4];
+  __shared__ unsigned sh[8];
   const int tid = threadIdx.x;
   const int b = find_seq(ct, st.batch, blockIdx.x);
   const int chunk = blockIdx.x - ct.off[b];
   const int c = blockIdx.y;
   const int n = st.n[b];
   const int nsegs = st.batch * h;
-  const int seg_head = b * h + c;
-  const int S = LAYER ? b : seg_head;
-  const unsigned prefix = prefix_g[S];
-  const int krem = krem_g[S];
-
   for (int i = tid; i < NB; i += 256) lh[i] = 0u;
+  const Rank r = rank_before_pass<P, LAYER>(st, h, b, c, budgets, hist, hist_tot, state, sh);
+  if (P >= 1 && chunk == 0 && (!LAYER || c == 0) && tid == 0)
+    state[(size_t)(P - 1) * nsegs + (LAYER ? b : b * h + c)] = make_uint2(r.prefix, (unsigned)r.krem);
   __syncthreads();
-  if (krem > 0) {
-    const float *row = scores + st.score_off[b] + (size_t)c * n;
-    const int j0 = chunk * SEL_CHUNK;
-    const int j1 = min(n, j0 + SEL_CHUNK);
-    for (int j = j0 + tid; j < j1; j += 256) {
-      const unsigned key = key_of(row[j]);
-      if (matches<P>(key, prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
-    }
+  if (r.krem <= 0) return;                             // nothing to select in this segment
+  const float *row = scores + st.score_off[b] + (size_t)c * n;
+  const int j0 = chunk * SEL_CHUNK;
+  const int j1 = min(n, j0 + SEL_CHUNK);
+  for (int j = j0 + tid; j < j1; j += 256) {
+    const unsigned key = key_of(row[j]);
+    if (matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
   }
   __syncthreads();
-  // Publish the block's counts and take a ticket WITHOUT a device-scope fence (on this part a
-  // release fence writes the whole L2 back, which costs more than the pass itself).  Everything
-  // other blocks read is written by device-scope atomics, which execute at the point of
-  // coherence; a returning atomic has been performed there once its value is back, so waiting
-  // for the returned values orders the counts in front of the ticket.
-  unsigned *gh = hist + ((size_t)P * nsegs + seg_head) * RADIX_BINS;
-  unsigned seen = 0u;
+  unsigned *gh = hist + ((size_t)P * nsegs + b * h + c) * RADIX_BINS;
+  unsigned *gt = hist_tot + ((size_t)P * st.batch + b) * RADIX_BINS;
   for (int i = tid; i < NB; i += 256) {
     const unsigned v = lh[i];
-    if (v) seen |= __hip_atomic_fetch_add(&gh[i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  asm volatile("" ::"v"(seen));          // the returned values are needed here: waits for them
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned nblk = (unsigned)(ct.off[b + 1] - ct.off[b]) * (LAYER ? (unsigned)h : 1u);
-    const unsigned t = __hip_atomic_fetch_add(&ticket[(size_t)P * nsegs + S], 1u, __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_AGENT);
-    sh_misc[0] = (t == nblk - 1u) ? 1u : 0u;
-  }
-  __syncthreads();
-  if (sh_misc[0] == 0u) return;
-
-  // ---- last block of this segment: choose the digit that holds the krem-th largest --------
-  const int c0 = LAYER ? 0 : c, c1 = LAYER ? h : c + 1;
-  constexpr int PER = NB / 256;                        // consecutive bins per thread
-  unsigned mine[PER];
-  unsigned my_sum = 0;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) mine[i] = 0u;
-  if (krem > 0) {
-    for (int cc = c0; cc < c1; ++cc) {
-      const unsigned *hh = hist + ((size_t)P * nsegs + b * h + cc) * RADIX_BINS + tid * PER;
-#pragma unroll
-      for (int i = 0; i < PER; ++i) mine[i] += ld_u32(hh + i);
+    if (v) {
+      atomicAdd(&gh[i], v);
+      if (LAYER) atomicAdd(&gt[i], v);
     }
-#pragma unroll
-    for (int i = 0; i < PER; ++i) my_sum += mine[i];
-  }
-  // inclusive suffix sum over threads: sh_scan[t] = sum of my_sum over threads >= t
-  sh_scan[tid] = my_sum;
-  __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {
-    const unsigned add = (tid + off < 256) ? sh_scan[tid + off] : 0u;
-    __syncthreads();
-    sh_scan[tid] += add;
-    __syncthreads();
-  }
-  if (tid < 64) sh_gt[tid] = 0;
-  if (tid == 0) { sh_misc[1] = 0xFFFFFFFFu; sh_misc[2] = 0u; sh_misc[3] = 0u; }
-  __syncthreads();
-  const unsigned above = sh_scan[tid] - my_sum;        // elements in bins owned by higher threads
-  if (krem > 0 && above < (unsigned)krem && (unsigned)krem <= above + my_sum) {
-    unsigned acc = above;
-    int dsel = 0;
-#pragma unroll
-    for (int i = PER - 1; i >= 0; --i) {
-      if (acc < (unsigned)krem && (unsigned)krem <= acc + mine[i]) { dsel = i; break; }
-      acc += mine[i];
-    }
-    sh_misc[1] = (unsigned)(tid * PER + dsel);         // chosen digit
-    sh_misc[2] = (unsigned)krem - acc;                 // rank inside that digit's bin (>= 1)
-  }
-  __syncthreads();
-  // (the clamp only matters for inputs outside the contract, e.g. NaN scores: it keeps every
-  // later read inside the histogram)
-  const unsigned dsel = min(sh_misc[1], (unsigned)(NB - 1));
-  const unsigned new_prefix = (krem > 0) ? with_digit<P>(prefix, dsel) : 0xFFFFFFFFu;
-  const int new_krem = (krem > 0) ? (int)sh_misc[2] : 0;
-  // per head: how many elements sit in bins above the chosen digit
-  if (krem > 0) {
-    for (int cc = c0; cc < c1; ++cc) {
-      const unsigned *hh = hist + ((size_t)P * nsegs + b * h + cc) * RADIX_BINS + tid * PER;
-      int cnt = 0;
-#pragma unroll
-      for (int i = 0; i < PER; ++i)
-        if ((unsigned)(tid * PER + i) > dsel) cnt += (int)ld_u32(hh + i);
-      if (cnt) atomicAdd(&sh_gt[cc - c0], cnt);
-    }
-  }
-  __syncthreads();
-  if (tid < c1 - c0) {
-    const int hidx = b * h + c0 + tid;
-    const int v = ld_i32(&gt[hidx]) + sh_gt[tid];
-    gt[hidx] = v;
-    sh_gt[tid] = v;
-  }
-  if (tid == 0) {
-    prefix_g[S] = new_prefix;
-    krem_g[S] = new_krem;
-  }
-  if (P != 2) return;
-  __syncthreads();
-  if (tid != 0) return;
-  if (!LAYER) {
-    thr_g[seg_head] = new_prefix;
-    ties_g[seg_head] = new_krem;
-    return;
-  }
-  // ---- Algorithm 1 counts f_c, then the safeguard (Alg. 2 l.8) in exact integers ----------
-  const long long Bp = st.Bp[b];
-  long long ties_left = new_krem;                      // threshold-valued elements still to take
-  const long long one = 65536, a = alpha_fix, den = one * h;
-  long long rem[64];
-  int base[64];
-  long long given = 0;
-  for (int cc = 0; cc < h; ++cc) {
-    long long eq = 0;
-    if (krem > 0)
-      eq = ld_u32(hist + ((size_t)2 * nsegs + b * h + cc) * RADIX_BINS + dsel);
-    const long long take = eq < ties_left ? eq : ties_left;
-    ties_left -= take;
-    const long long f = (long long)sh_gt[cc] + take;
-    const long long num = (one - a) * h * f + a * Bp;
-    base[cc] = (int)(num / den);
-    rem[cc] = num % den;
-    given += base[cc];
-  }
-  int left = (int)(Bp - given);                        // 0 <= left < h
-  while (left > 0) {
-    int best = 0;
-    for (int cc = 1; cc < h; ++cc)
-      if (rem[cc] > rem[best]) best = cc;              // strict: ties stay with the lower head
-    base[best] += 1;
-    rem[best] = -1;
-    --left;
-  }
-  int run = st.out_off[b];
-  if (b == 0) cu[0] = 0;
-  for (int cc = 0; cc < h; ++cc) {
-    budgets[b * h + cc] = base[cc];
-    run += base[cc] + w;
-    cu[b * h + cc + 1] = run;
   }
 }
 
+// Layer scope, after the third pass: Algorithm 1's counts f_c and the safeguard of Alg. 2 l.8.
+// One block per sequence.
+__global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int w, int alpha_fix,
+                                                           const unsigned *__restrict__ hist,
+                                                           const unsigned *__restrict__ hist_tot,
+                                                           const uint2 *__restrict__ state,
+                                                           int *__restrict__ budgets,
+                                                           int *__restrict__ cu) {
+  __shared__ unsigned sh[8];
+  __shared__ int sh_gt[64], sh_eq[64];
+  const int tid = threadIdx.x;
+  const int b = blockIdx.x;
+  const int nsegs = st.batch * h;
+  if (tid < 64) { sh_gt[tid] = 0; sh_eq[tid] = 0; }
+  const Rank r = rank_before_pass<3, true>(st, h, b, 0, nullptr, hist, hist_tot, state, sh);
+  __syncthreads();
+  // r.prefix is the threshold key, r.krem how many threshold-valued elements are taken (in
+  // flat-index order, i.e. head by head).  Per head: elements strictly above the threshold are
+  // those in higher bins of pass 0, plus higher bins of pass 1 under the same first digit, ...
+  // Wavefront wv takes heads wv, wv+4, ...; a lane loads all its bins of the three histograms
+  // of a head at once (20 independent 16-byte loads), so a head costs one memory round trip.
+  if (r.krem > 0) {
+    const unsigned d0 = digit_of<0>(r.prefix), d1 = digit_of<1>(r.prefix), d2 = digit_of<2>(r.prefix);
+    const int lane = tid & 63, wv = tid >> 6;
+    for (int c = wv; c < h; c += 4) {
+      const uint4 *b0 = reinterpret_cast<const uint4 *>(hist + ((size_t)0 * nsegs + b * h + c) * RADIX_BINS) + lane * 8;
+      const uint4 *b1 = reinterpret_cast<const uint4 *>(hist + ((size_t)1 * nsegs + b * h + c) * RADIX_BINS) + lane * 8;
+      const uint4 *b2 = reinterpret_cast<const uint4 *>(hist + ((size_t)2 * nsegs + b * h + c) * RADIX_BINS) + lane * 4;
+      uint4 v0[8], v1[8], v2[4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { v0[i] = b0[i]; v1[i] = b1[i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v2[i] = b2[i];
+      int cnt = 0, eq = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const unsigned a0[4] = {v0[i].x, v0[i].y, v0[i].z, v0[i].w};
+        const unsigned a1[4] = {v1[i].x, v1[i].y, v1[i].z, v1[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const unsigned bin = (unsigned)(lane * 32 + i * 4 + k);
+          if (bin > d0) cnt += (int)a0[k];
+          if (bin > d1) cnt += (int)a1[k];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const unsigned a2[4] = {v2[i].x, v2[i].y, v2[i].z, v2[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const unsigned bin = (unsigned)(lane * 16 + i * 4 + k);
+          if (bin > d2) cnt += (int)a2[k];
+          if (bin == d2) eq += (int)a2[k];
+        }
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) { cnt += __shfl_xor(cnt, off); eq += __shfl_xor(eq, off); }
+      if (lane == 0) { sh_gt[c] = cnt; sh_eq[c] = eq; }
+    }
+  }
+  __syncthreads();
+  // One lane per head (h <= 64): every step below is a count over the other heads, so the lanes
+  // never wait for each other and the 64-bit divisions run side by side.
+  if (tid >= 64) return;
+  __shared__ long long sh_rem[64];
+  __shared__ int sh_base[64];
+  const int c = tid;
+  const bool live = c < h;
+  const long long Bp = st.Bp[b];
+  const long long one = 65536, a = alpha_fix, den = one * h;
+  long long rem = -1;
+  int base = 0;
+  if (live) {
+    long long before = 0;                              // threshold-valued elements of earlier heads
+    for (int i = 0; i < c; ++i) before += sh_eq[i];
+    long long avail = (long long)r.krem - before;      // ties still to take when head c's turn comes
+    if (avail < 0) avail = 0;
+    const long long take = sh_eq[c] < avail ? sh_eq[c] : avail;
+    const long long f = (long long)sh_gt[c] + take;     // Algorithm 1: B*_c = f_c
+    const long long num = (one - a) * h * f + a * Bp;   // x_c = num / den
+    base = (int)(num / den);
+    rem = num - (long long)base * den;
+  }
+  sh_rem[c] = rem;
+  sh_base[c] = base;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  if (!live) return;
+  long long given = 0;
+  int rank = 0;                                        // heads that come first for a spare unit
+  for (int i = 0; i < h; ++i) {
+    given += sh_base[i];
+    rank += (sh_rem[i] > rem) || (sh_rem[i] == rem && i < c);
+  }
+  const int left = (int)(Bp - given);                  // 0 <= left < h
+  if (rank < left) base += 1;                          // largest remainders, ties to the lower head
+  budgets[b * h + c] = base;
+  sh_base[c] = base;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  int run = st.out_off[b];
+  for (int i = 0; i <= c; ++i) run += sh_base[i] + w;
+  if (b == 0 && c == 0) cu[0] = 0;
+  cu[b * h + c + 1] = run;
+}
+
 // Exclusive prefix sums of two per-thread counts over the 256 threads of a block.
-__device__ __forceinline__ void block_scan2(int a, int b, int &ea, int &eb, int *sh /*[16]*/) {
+__device__ __forceinline__ void block_scan2(int a, int b, int &ea, int &eb, int *sh /*[8]*/) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   int ia = a, ib = b;
 #pragma unroll
@@ -272,30 +310,42 @@ __device__ __forceinline__ void block_scan2(int a, int b, int &ea, int &eb, int 
     const int ua = __shfl_up(ia, off), ub = __shfl_up(ib, off);
     if (lane >= off) { ia += ua; ib += ub; }
   }
+  __syncthreads();
   if (lane == 63) { sh[wv] = ia; sh[4 + wv] = ib; }
   __syncthreads();
   int ba = 0, bb = 0;
   for (int i = 0; i < wv; ++i) { ba += sh[i]; bb += sh[4 + i]; }
   ea = ba + ia - a;
   eb = bb + ib - b;
-  __syncthreads();
 }
 
 constexpr int EPT = SEL_CHUNK / 256;   // consecutive positions per thread in the emit kernels
 
+// Head scope, after the third pass: (threshold key, number of threshold-valued positions to take)
+__device__ __forceinline__ Rank head_threshold(const SeqTab &st, int h, int b, int c,
+                                               const unsigned *__restrict__ hist,
+                                               const uint2 *__restrict__ state, unsigned *sh) {
+  Rank r = rank_before_pass<3, false>(st, h, b, c, nullptr, hist, nullptr, state, sh);
+  if (r.krem <= 0) { r.prefix = 0xFFFFFFFFu; r.krem = 0; }   // no key is above, no tie is taken
+  return r;
+}
+
 __global__ __launch_bounds__(256) void emit_count_kernel(SeqTab st, ChunkTab ct, int h,
                                                          const float *__restrict__ scores,
-                                                         const unsigned *__restrict__ thr_g,
+                                                         const unsigned *__restrict__ hist,
+                                                         const uint2 *__restrict__ state,
                                                          int *__restrict__ chunk_cnt) {
-  __shared__ int sh[2];
+  __shared__ unsigned sh[8];
+  __shared__ int tot[2];
   const int tid = threadIdx.x;
   const int b = find_seq(ct, st.batch, blockIdx.x);
   const int chunk = blockIdx.x - ct.off[b];
   const int c = blockIdx.y;
   const int n = st.n[b];
-  const unsigned thr = thr_g[b * h + c];
+  if (tid < 2) tot[tid] = 0;
+  const Rank r = head_threshold(st, h, b, c, hist, state, sh);
+  const unsigned thr = r.prefix;
   const float *row = scores + st.score_off[b] + (size_t)c * n;
-  if (tid < 2) sh[tid] = 0;
   __syncthreads();
   int g = 0, e = 0;
   const int j0 = chunk * SEL_CHUNK, j1 = min(n, j0 + SEL_CHUNK);
@@ -306,17 +356,17 @@ __global__ __launch_bounds__(256) void emit_count_kernel(SeqTab st, ChunkTab ct,
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) { g += __shfl_xor(g, off); e += __shfl_xor(e, off); }
-  if ((tid & 63) == 0) { atomicAdd(&sh[0], g); atomicAdd(&sh[1], e); }
+  if ((tid & 63) == 0) { atomicAdd(&tot[0], g); atomicAdd(&tot[1], e); }
   __syncthreads();
-  if (tid < 2) chunk_cnt[((size_t)blockIdx.x * h + c) * 2 + tid] = sh[tid];
+  if (tid < 2) chunk_cnt[((size_t)blockIdx.x * h + c) * 2 + tid] = tot[tid];
 }
 
 __global__ __launch_bounds__(256) void emit_write_kernel(
     SeqTab st, ChunkTab ct, int h, int w, const float *__restrict__ scores,
-    const unsigned *__restrict__ thr_g, const int *__restrict__ ties_g,
+    const unsigned *__restrict__ hist, const uint2 *__restrict__ state,
     const int *__restrict__ chunk_cnt, const int *__restrict__ budgets,
     const int *__restrict__ cu, int *__restrict__ indices, int rows_total) {
-  __shared__ int sh[16];
+  __shared__ unsigned sh[8];
   __shared__ int sh_base[2];
   const int tid = threadIdx.x;
   const int b = find_seq(ct, st.batch, blockIdx.x);
@@ -324,10 +374,14 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
   const int c = blockIdx.y;
   const int n = st.n[b];
   const int seg = b * h + c;
-  const unsigned thr = thr_g[seg];
-  const int ties = ties_g[seg];
   const int out0 = cu[seg];
   const float *row = scores + st.score_off[b] + (size_t)c * n;
+
+  // this thread's 16 consecutive positions (loads issued before the scans below)
+  const int j0 = chunk * SEL_CHUNK + tid * EPT;
+  unsigned keys[EPT];
+#pragma unroll
+  for (int i = 0; i < EPT; ++i) keys[i] = (j0 + i < n) ? key_of(row[j0 + i]) : 0u;
 
   // what the earlier chunks of this head hold above / at the threshold
   int pg = 0, pe = 0;
@@ -337,27 +391,24 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
     pe += cc[1];
   }
   if (tid < 2) sh_base[tid] = 0;
+  const Rank r = head_threshold(st, h, b, c, hist, state, sh);
+  const unsigned thr = r.prefix;
+  const int ties = r.krem;
   __syncthreads();
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) { pg += __shfl_xor(pg, off); pe += __shfl_xor(pe, off); }
   if ((tid & 63) == 0) { atomicAdd(&sh_base[0], pg); atomicAdd(&sh_base[1], pe); }
-  __syncthreads();
-  const int base_g = sh_base[0], base_e = sh_base[1];
 
-  const int j0 = chunk * SEL_CHUNK + tid * EPT;
-  unsigned keys[EPT];
   int g = 0, e = 0;
 #pragma unroll
   for (int i = 0; i < EPT; ++i) {
-    const int j = j0 + i;
-    keys[i] = (j < n) ? key_of(row[j]) : 0u;
-    const bool valid = j < n;
+    const bool valid = j0 + i < n;
     g += valid && keys[i] > thr;
     e += valid && keys[i] == thr;
   }
   int eg, ee;
-  block_scan2(g, e, eg, ee, sh);
-  int ng = base_g + eg, ne = base_e + ee;   // counts over all earlier positions of the head
+  block_scan2(g, e, eg, ee, (int *)sh);                // its barriers also publish sh_base
+  int ng = sh_base[0] + eg, ne = sh_base[1] + ee;      // counts over all earlier positions of the head
 #pragma unroll
   for (int i = 0; i < EPT; ++i) {
     const int j = j0 + i;
@@ -370,8 +421,8 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
   }
   if (chunk == 0) {
     const int bud = budgets[seg];
-    for (int r = tid; r < w; r += 256)
-      if (out0 + bud + r < rows_total) indices[out0 + bud + r] = n + r;
+    for (int rr = tid; rr < w; rr += 256)
+      if (out0 + bud + rr < rows_total) indices[out0 + bud + rr] = n + rr;
   }
 }
 
@@ -380,57 +431,55 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
 size_t plan_topk_bytes(const SeqTab &st, const Dims &dm) { return plan(st, dm).total; }
 
 template <bool LAYER>
-static hipError_t run_passes(const SeqTab &st, const Dims &dm, const float *scores,
-                             const int *budgets_in, int *budgets_out, int *cu, char *ws,
-                             hipStream_t s) {
-  const TopkWs p = plan(st, dm);
-  const ChunkTab ct = make_chunks(st, SEL_CHUNK);
+static void run_passes(const SeqTab &st, const Dims &dm, const float *scores,
+                       const int *budgets_in, const TopkWs &p, const ChunkTab &ct, char *ws,
+                       hipStream_t s) {
   const int h = dm.h_kv;
   unsigned *hist = (unsigned *)(ws + p.hist);
-  unsigned *ticket = (unsigned *)(ws + p.ticket);
-  int *gt = (int *)(ws + p.gt);
-  unsigned *prefix = (unsigned *)(ws + p.prefix);
-  int *krem = (int *)(ws + p.krem);
-  unsigned *thr = (unsigned *)(ws + p.thr);
-  int *ties = (int *)(ws + p.ties);
+  unsigned *hist_tot = (unsigned *)(ws + p.hist_tot);
+  uint2 *state = (uint2 *)(ws + p.state);
   const size_t zero_words = p.zero_end / 4;
-  int zb = (int)((zero_words + 256 * 8 - 1) / (256 * 8));
+  int zb = (int)((zero_words + 256 * 4 - 1) / (256 * 4));
   if (zb < 1) zb = 1;
   if (zb > 1024) zb = 1024;
-  ADAKV_LAUNCH(LAYER ? "alloc_init" : "select_init", topk_init_kernel, dim3(zb), dim3(256), s, st,
-               h, LAYER, budgets_in,
-                     (unsigned *)ws, zero_words, prefix, krem);
+  ADAKV_LAUNCH(LAYER ? "alloc_init" : "select_init", topk_init_kernel, dim3(zb), dim3(256), s,
+               (unsigned *)ws, zero_words);
   dim3 grid(ct.off[st.batch], h), block(256);
 #define ADAKV_PASS(P)                                                                          \
-  ADAKV_LAUNCH(LAYER ? "alloc_pass" #P : "select_pass" #P, (topk_pass_kernel<P, LAYER>), grid,   \
-               block, s, st, ct, h, dm.w, dm.alpha_fix, scores, hist, ticket, gt, prefix, krem,  \
-               thr, ties, budgets_out, cu)
+  ADAKV_LAUNCH(LAYER ? "alloc_pass" #P : "select_pass" #P, (topk_hist_kernel<P, LAYER>), grid,   \
+               block, s, st, ct, h, scores, budgets_in, hist, hist_tot, state)
   ADAKV_PASS(0);
   ADAKV_PASS(1);
   ADAKV_PASS(2);
 #undef ADAKV_PASS
-  return hipGetLastError();
 }
 
 hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores, int *budgets,
                            int *cu_seqlens, char *ws, hipStream_t s) {
-  return run_passes<true>(st, dm, scores, nullptr, budgets, cu_seqlens, ws, s);
+  const TopkWs p = plan(st, dm);
+  const ChunkTab ct = make_chunks(st, SEL_CHUNK);
+  run_passes<true>(st, dm, scores, nullptr, p, ct, ws, s);
+  ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(256), s, st, dm.h_kv,
+               dm.w, dm.alpha_fix, (const unsigned *)(ws + p.hist),
+               (const unsigned *)(ws + p.hist_tot), (const uint2 *)(ws + p.state), budgets,
+               cu_seqlens);
+  return hipGetLastError();
 }
 
 hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
                          const int *budgets, const int *cu_seqlens, int *indices, char *ws,
                          hipStream_t s) {
-  hipError_t e = run_passes<false>(st, dm, scores, budgets, nullptr, nullptr, ws, s);
-  if (e != hipSuccess) return e;
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
+  run_passes<false>(st, dm, scores, budgets, p, ct, ws, s);
   dim3 grid(ct.off[st.batch], dm.h_kv), block(256);
   ADAKV_LAUNCH("select_count", emit_count_kernel, grid, block, s, st, ct, dm.h_kv, scores,
-                     (const unsigned *)(ws + p.thr), (int *)(ws + p.chunk_cnt));
+               (const unsigned *)(ws + p.hist), (const uint2 *)(ws + p.state),
+               (int *)(ws + p.chunk_cnt));
   ADAKV_LAUNCH("select_emit", emit_write_kernel, grid, block, s, st, ct, dm.h_kv, dm.w, scores,
-                     (const unsigned *)(ws + p.thr), (const int *)(ws + p.ties),
-                     (const int *)(ws + p.chunk_cnt), budgets, cu_seqlens, indices,
-                     st.out_off[st.batch]);
+               (const unsigned *)(ws + p.hist), (const uint2 *)(ws + p.state),
+               (const int *)(ws + p.chunk_cnt), budgets, cu_seqlens, indices,
+               st.out_off[st.batch]);
   return hipGetLastError();
 }
 

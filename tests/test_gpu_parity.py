@@ -164,6 +164,20 @@ def test_select_with_zero_budget_heads_and_full_heads():
     assert np.array_equal(idx.cpu().numpy(), O.select(s, budgets, w))
 
 
+def test_select_long_heads_take_the_chunk_parallel_emit():
+    # heads longer than 262144 positions are emitted by the two chunk-parallel kernels instead of
+    # by the block that finishes the last radix pass
+    _say("select long heads")
+    rng = np.random.default_rng(8)
+    h, n, w = 2, 300001, 4
+    s = O.max_pool_same((rng.random((h, n)) ** 12).astype(np.float32), 7)
+    for alpha, B in ((0.2, w * h + 20000), (0.0, w * h + 3)):
+        bud, cu, idx = _alloc_select(s, w, B, alpha)
+        rb, rcu = O.allocate(s, B, w, alpha)
+        assert np.array_equal(bud, rb) and np.array_equal(cu, rcu)
+        assert np.array_equal(idx, O.select(s, rb, w))
+
+
 # ------------------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("dt,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)])
 def test_compact_bit_exact_with_strides_and_canaries(dt, d):
