@@ -14,8 +14,9 @@
 // operands for the whole chunk (MB blocks of 32 rows), which leaves room for two wavefronts per
 // SIMD, so one wavefront's exponentials overlap the other's matrix work.  RS wavefronts split
 // the rows of a head, and the KG = NW/RS groups of wavefronts take the 32-key tiles of the
-// chunk in turn.  A K tile travels HBM -> registers (coalesced 16-byte loads of whole rows) ->
-// the wavefront's own LDS slot (padded rows) -> registers in operand layout.
+// chunk in turn.  A K tile travels HBM -> registers (coalesced 16-byte loads of whole rows,
+// issued by the whole workgroup, two iterations ahead) -> LDS (padded rows, shared by the
+// wavefronts that need the tile) -> registers in operand layout.
 //
 // Operand roles differ between the sweeps because of what the accumulator layout makes cheap
 // (D[i][j]: lane = column j, 16 rows i per lane):
@@ -55,12 +56,10 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   constexpr int KS = D / 16;                 // MFMA k-steps per tile
   constexpr int ROW16 = D * 2 / 16;          // 16-byte words per K row
   constexpr int STRIDE16 = ROW16 + 1;        // padded LDS row, in 16-byte words
-  constexpr int RPI = 64 / ROW16;            // rows per load instruction
-  constexpr int NLD = TILE / RPI;            // load instructions per tile
   constexpr int RW = 32 * MB;                // window rows per wavefront
   constexpr int RPAD = RW * RS;              // window rows per workgroup (padded)
 
-  __shared__ u32x4 kt[NW][TILE * STRIDE16];  // one K tile slot per wavefront
+  __shared__ u32x4 kt[2][KG * TILE * STRIDE16];  // two buffers of one iteration's KG tiles
   __shared__ float sh_rows[2][NW][RW];       // sweep 1: per-wave row (max, sum); sweep 2: [0][0] lse
   constexpr int HALO = TILE;                 // keys scored on either side of the chunk for the pool
   __shared__ float sh_part[PASS == 2 ? RS : 1][PASS == 2 ? CHUNK + 2 * HALO : 1];
@@ -154,42 +153,56 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) { rm[mb] = -INFINITY; rl[mb] = 0.0f; }
 
-  // K addressing: a wave-uniform 64-bit base per tile (scalar registers) plus a 32-bit per-lane
-  // offset, so the vector ALU does no address arithmetic inside the loop.
+  // ---- K path ---------------------------------------------------------------------------------
+  // An iteration covers KG consecutive tiles (one per wavefront group).  All threads of the
+  // workgroup load the iteration's rows together: 16 lanes per 256-byte row, every byte read
+  // once per workgroup, addressed as a wave-uniform 64-bit base (scalar registers) plus a
+  // 32-bit per-lane offset.  The loads of iterations it+1 and it+2 are in flight while
+  // iteration it is computed (two register sets, two LDS buffers, one barrier per iteration).
+  constexpr int TW = TILE * ROW16;                     // 16-byte words per tile
+  constexpr int LDPT = KG * TW / NT;                   // loads per thread per iteration
+  static_assert(KG * TW % NT == 0 && LDPT >= 1, "tile set must split evenly over the threads");
   const char *kbase = reinterpret_cast<const char *>(K) +
                       ((size_t)st.tok_off[b] * dm.k_stride_tok + (size_t)c * dm.k_stride_head) * 2;
   const size_t tok_bytes = (size_t)dm.k_stride_tok * 2;
-  const int ld_row = lane / ROW16, ld_col = lane % ROW16;
-  const unsigned lane_off = (unsigned)ld_row * (unsigned)tok_bytes + (unsigned)ld_col * 16u;
-  u32x4 *slot = kt[wv];
-  const int wr_off = ld_row * STRIDE16 + ld_col;
-  const int rd_off = l32 * STRIDE16 + half;
+  // word tid + i*NT of the iteration's KG*TW words: row (relative to the iteration's first key)
+  // and 16-byte column
+  int ld_rel[LDPT];
+  int wr_off[LDPT];                                    // word offset in an LDS buffer
+  const unsigned col_bytes = (unsigned)(tid % ROW16) * 16u;
+#pragma unroll
+  for (int i = 0; i < LDPT; ++i) {
+    const int wi = tid + i * NT;
+    const int tl = wi / TW, row = (wi % TW) / ROW16;
+    ld_rel[i] = tl * TILE + row;
+    wr_off[i] = tl * (TILE * STRIDE16) + row * STRIDE16 + tid % ROW16;
+  }
+  const int rd_off = kg * (TILE * STRIDE16) + l32 * STRIDE16 + half;
+  const int iters = (ntiles + KG - 1) / KG;
+  // The workgroups of a head run side by side and their chunks lie a fixed power-of-two number
+  // of bytes apart; if all of them walked their chunk from its first row, they would ask for
+  // addresses that are equal modulo that distance at the same time, i.e. the same memory
+  // channels.  Each workgroup therefore starts at a different point of its chunk and wraps
+  // around (neither sweep depends on the order of the tiles).
+  const int rot = (int)(((long long)chunk * iters) / (ct.off[b + 1] - ct.off[b]));
+  auto phys = [&](int it) { const int p = it + rot; return p >= iters ? p - iters : p; };
 
-  u32x4 g[NLD];
-  // full tile: all 32 rows exist
-  auto load_full = [&](int tile) {
-    const char *tb = kbase + (size_t)(k0 + tile * TILE) * tok_bytes;
+  // Branch-free on purpose (the compiler can only keep older loads in flight across a wait if
+  // the loads in between are issued on every path): rows past the end of the sequence re-read
+  // row n-1 and are masked out later.  tok_bytes < 2^24 is checked on the host.
+  auto load_set = [&](u32x4 (&g)[LDPT], int it) {
+    const int key0 = k0 + it * KG * TILE;              // first key of the iteration
+    const int lim = n - 1 - key0;
+    const char *sb = kbase + (size_t)key0 * tok_bytes;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i)
-      g[i] = *reinterpret_cast<const u32x4 *>(tb + (size_t)(i * RPI) * tok_bytes + lane_off);
-  };
-  // last tile of a sequence: rows past the end re-read row n-1 (masked out later)
-  auto load_ragged = [&](int tile) {
-    const int base_ = k0 + tile * TILE + ld_row;
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int key_ = min(base_ + i * RPI, n - 1);
-      g[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key_ * tok_bytes + ld_col * 16);
+    for (int i = 0; i < LDPT; ++i) {
+      const unsigned off = __umul24((unsigned)min(ld_rel[i], lim), (unsigned)tok_bytes) + col_bytes;
+      g[i] = *reinterpret_cast<const u32x4 *>(sb + off);
     }
   };
-  auto load_tile = [&](int tile) {
-    if (k0 + tile * TILE + TILE <= n) load_full(tile); else load_ragged(tile);
-  };
-  auto store_tile = [&]() {
+  auto store_set = [&](const u32x4 (&g)[LDPT], int buf) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) slot[wr_off + i * RPI * STRIDE16] = g[i];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    for (int i = 0; i < LDPT; ++i) kt[buf][wr_off[i]] = g[i];
   };
 
   // one 32-key tile against this wavefront's rows; RAGGED masks keys at or past n
@@ -238,25 +251,34 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     }
   };
 
-  // this wavefront's tiles: kg, kg + KG, ...  The next tile's loads fly during the math.
-  int tile = kg;
-  if (tile < ntiles) {
-    load_tile(tile);
-    store_tile();
-  }
-  while (tile < ntiles) {
-    // LDS slot -> operand layout (the same wavefront wrote it; LDS operations of one wavefront
-    // complete in order)
+  // iteration it: LDS buffer it%2 holds its tiles, register set gb is in flight with it+1's,
+  // set ga is free and takes it+2's
+  auto step = [&](int it, u32x4 (&ga)[LDPT], u32x4 (&gb)[LDPT]) {
     bf16x8 kf[KS];
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const u32x4 *buf = kt[it & 1];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) kf[s] = as_bf16(slot[rd_off + s * 2]);
-    const int next = tile + KG;
-    if (next < ntiles) load_tile(next);
-    if (k0 + tile * TILE + TILE <= n) compute(std::false_type{}, kf, tile);
-    else compute(std::true_type{}, kf, tile);
-    if (next < ntiles) store_tile();
-    tile = next;
+    for (int s = 0; s < KS; ++s) kf[s] = as_bf16(buf[rd_off + s * 2]);
+    // always issued (the last iterations re-read the final set): a conditional load would make
+    // the compiler wait for every outstanding load before the stores below
+    load_set(ga, phys(min(it + 2, iters - 1)));
+    const int tile = phys(it) * KG + kg;
+    if (tile < ntiles) {
+      if (k0 + tile * TILE + TILE <= n) compute(std::false_type{}, kf, tile);
+      else compute(std::true_type{}, kf, tile);
+    }
+    if (it + 1 < iters) store_set(gb, (it + 1) & 1);
+    __syncthreads();
+  };
+  {
+    u32x4 g0[LDPT], g1[LDPT];
+    load_set(g0, phys(0));
+    load_set(g1, phys(min(1, iters - 1)));
+    store_set(g0, 0);
+    __syncthreads();
+    for (int it = 0; it < iters; it += 2) {
+      step(it, g0, g1);
+      if (it + 1 < iters) step(it + 1, g1, g0);
+    }
   }
 
   if (PASS == 1) {
@@ -352,14 +374,18 @@ void run_mfma_d(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   else if (R <= 64) run_mfma<D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
   else if (R <= 128) run_mfma<D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
   else if (R <= 256) run_mfma<D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else run_mfma<D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
+  // a tile half the loads, so four wavefronts of 128 rows
+  else if constexpr (D == 128) run_mfma<D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else run_mfma<D, 4, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
 }
 
 }  // namespace
 
 // bf16 inputs with at most 512 window rows per KV head (g*w); anything else takes the FMA path.
 bool mfma_path_supported(const Dims &dm, int dtype) {
-  return dtype == ADAKV_BF16 && dm.g * dm.w <= 512 && (dm.d == 64 || dm.d == 128);
+  return dtype == ADAKV_BF16 && dm.g * dm.w <= 512 && (dm.d == 64 || dm.d == 128) &&
+         dm.k_stride_tok * 2 < (1ll << 24);   // 24-bit multiplies address a row inside a tile set
 }
 
 hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
