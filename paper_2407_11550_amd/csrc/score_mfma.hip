@@ -157,8 +157,8 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // An iteration covers KG consecutive tiles (one per wavefront group).  All threads of the
   // workgroup load the iteration's rows together: 16 lanes per 256-byte row, every byte read
   // once per workgroup, addressed as a wave-uniform 64-bit base (scalar registers) plus a
-  // 32-bit per-lane offset.  The loads of iterations it+1 and it+2 are in flight while
-  // iteration it is computed (two register sets, two LDS buffers, one barrier per iteration).
+  // 32-bit per-lane offset.  The loads of iterations it+1, it+2 and it+3 are in flight while
+  // iteration it is computed (three register sets, two LDS buffers, one barrier per iteration).
   constexpr int TW = TILE * ROW16;                     // 16-byte words per tile
   constexpr int LDPT = KG * TW / NT;                   // loads per thread per iteration
   static_assert(KG * TW % NT == 0 && LDPT >= 1, "tile set must split evenly over the threads");
@@ -251,8 +251,8 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     }
   };
 
-  // iteration it: LDS buffer it%2 holds its tiles, register set gb is in flight with it+1's,
-  // set ga is free and takes it+2's
+  // iteration it: LDS buffer it%2 holds its tiles; register sets gb and gc are in flight with the
+  // loads of it+1 and it+2; set ga is free and takes it+3's
   auto step = [&](int it, u32x4 (&ga)[LDPT], u32x4 (&gb)[LDPT]) {
     bf16x8 kf[KS];
     const u32x4 *buf = kt[it & 1];
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     for (int s = 0; s < KS; ++s) kf[s] = as_bf16(buf[rd_off + s * 2]);
     // always issued (the last iterations re-read the final set): a conditional load would make
     // the compiler wait for every outstanding load before the stores below
-    load_set(ga, phys(min(it + 2, iters - 1)));
+    load_set(ga, phys(min(it + 3, iters - 1)));
     const int tile = phys(it) * KG + kg;
     if (tile < ntiles) {
       if (k0 + tile * TILE + TILE <= n) compute(std::false_type{}, kf, tile);
@@ -270,14 +270,16 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     __syncthreads();
   };
   {
-    u32x4 g0[LDPT], g1[LDPT];
+    u32x4 g0[LDPT], g1[LDPT], g2[LDPT];
     load_set(g0, phys(0));
     load_set(g1, phys(min(1, iters - 1)));
+    load_set(g2, phys(min(2, iters - 1)));
     store_set(g0, 0);
     __syncthreads();
-    for (int it = 0; it < iters; it += 2) {
+    for (int it = 0; it < iters; it += 3) {
       step(it, g0, g1);
-      if (it + 1 < iters) step(it + 1, g1, g0);
+      if (it + 1 < iters) step(it + 1, g1, g2);
+      if (it + 2 < iters) step(it + 2, g2, g0);
     }
   }
 
