@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X published peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# (workload, kernel) -> fetched + written bytes per launch, see profiles/llama8b_128k_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {
+    ("llama8b_128k", "score_stats_mfma"): int((256.43 + 0.50) * 2 ** 20),
+    ("llama8b_128k", "score_weights_mfma"): int((257.22 + 4.00) * 2 ** 20),
+}
 
 
 def algorithmic_bytes(wl, kept_rows):
@@ -48,6 +53,8 @@ def main():
     ap.add_argument("--alpha", type=float, default=None)
     ap.add_argument("--sets", type=int, default=5, help="distinct input sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB device-to-device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); "
@@ -73,6 +80,14 @@ def main():
                 indices=torch.empty(layer.num_rows_out, dtype=torch.int32, device=dev),
                 K_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev),
                 V_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev))
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step(i):
         q, K, V = sets[i % len(sets)]
@@ -118,30 +133,39 @@ def main():
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     total_alg = alg["score"] + alg["allocate"] + alg["select"] + alg["compact"]
     flops = 2.0 * wl.g * wl.w * wl.d * wl.h_kv * tokens
+    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+    # counters read for a 1 GiB copy (profiles/llama8b_128k_hbm_traffic.md); only for the
+    # workload and kernels that were profiled
+    traffic = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant))
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
+                "traffic": traffic, "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
 
-    # ---- the oracle on the host cores, same layer (one full layer call) ---------------------
+    # ---- the oracle on the host cores: whole layers of the same workload, about 10 s ----------
     cpu = None
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
 
         from oracle import adakv_oracle as O
-        q, K, V = sets[0]
-        b_n, b_B = wl.n[0], wl.B[0]
         off = wl.tok_off
-        qd = q[0].double().cpu().numpy()
-        Kd = K[off[0]:off[1]].double().cpu().numpy()
-        Vd = V[off[0]:off[1]].float().cpu().numpy()
-        c0 = time.perf_counter()
-        O.compress_layer(qd, Kd, Vd, b_n, wl.w, wl.pool_k, b_B, wl.alpha)
-        c1 = time.perf_counter()
+        done_tokens, layers_done, spent = 0, 0, 0.0
+        while spent < 10.0 and layers_done < 64:
+            q, K, V = sets[layers_done % len(sets)]
+            for b in range(wl.batch):
+                qd = q[b].double().cpu().numpy()
+                Kd = K[off[b]:off[b + 1]].double().cpu().numpy()
+                Vd = V[off[b]:off[b + 1]].float().cpu().numpy()
+                c0 = time.perf_counter()
+                O.compress_layer(qd, Kd, Vd, wl.n[b], wl.w, wl.pool_k, wl.B[b], wl.alpha)
+                spent += time.perf_counter() - c0
+                done_tokens += wl.n[b]
+            layers_done += 1
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        cpu = {"value": round(b_n / (c1 - c0), 1), "unit": "prefix tokens/s", "cores": threads,
-               "kind": "oracle", "seconds": round(c1 - c0, 3),
-               "sample": f"one full layer call (sequence 0 of {wl.name}: n={b_n}, all four steps), "
-                         f"fp64 numpy; BLAS threads={threads} for the logit matmuls, the rest single-threaded"}
+        cpu = {"value": round(done_tokens / spent, 1), "unit": "prefix tokens/s", "cores": threads,
+               "kind": "oracle", "seconds": round(spent, 3),
+               "sample": f"{layers_done} whole layer call(s) of {wl.name} (all four steps, {done_tokens} prefix "
+                         f"tokens), fp64 numpy; {threads} BLAS threads for the logit matmuls, the rest "
+                         "single-threaded; upcasting the inputs to fp64 is not timed"}
 
     out = {
         "metric": "prefix tokens compressed/sec per layer (score+allocate+select+compact)",
