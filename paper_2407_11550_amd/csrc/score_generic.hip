@@ -159,22 +159,32 @@ __global__ __launch_bounds__(256) void raw_generic_kernel(
 
 }  // namespace
 
-// lse[b][row] = log of the sum over the sequence's chunks of l * exp(m), one thread per row.
+// lse[b][row] = log of the sum over the sequence's chunks of l * exp(m).  One wavefront per row:
+// the lanes stride over the chunks (independent loads), then the 64 partial (max, sum) pairs are
+// merged with shuffles.
 __global__ __launch_bounds__(256) void lse_combine_kernel(SeqTab st, ChunkTab ct, int RQ,
                                                           const float *__restrict__ part_m,
                                                           const float *__restrict__ part_l,
                                                           float *__restrict__ lse) {
-  const int row = blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int b = blockIdx.y;
   if (row >= RQ) return;
-  float M = -INFINITY;
-  for (int k = ct.off[b]; k < ct.off[b + 1]; ++k) M = fmaxf(M, part_m[(size_t)k * RQ + row]);
-  float L = 0.0f;
-  for (int k = ct.off[b]; k < ct.off[b + 1]; ++k) {
-    const float m = part_m[(size_t)k * RQ + row];
-    if (m > -INFINITY) L += part_l[(size_t)k * RQ + row] * expf(m - M);
+  float M = -INFINITY, L = 0.0f;
+  for (int k = ct.off[b] + lane; k < ct.off[b + 1]; k += 64) {
+    const float m = part_m[(size_t)k * RQ + row], l = part_l[(size_t)k * RQ + row];
+    const float nm = fmaxf(M, m);
+    if (nm > -INFINITY) L = L * expf(M - nm) + l * expf(m - nm);
+    M = nm;
   }
-  lse[(size_t)b * RQ + row] = M + logf(L);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float m2 = __shfl_xor(M, off), l2 = __shfl_xor(L, off);
+    const float nm = fmaxf(M, m2);
+    if (nm > -INFINITY) L = L * expf(M - nm) + l2 * expf(m2 - nm);
+    M = nm;
+  }
+  if (lane == 0) lse[(size_t)b * RQ + row] = M + logf(L);
 }
 
 // scores[j] = max of raw over [j - k/2, j + k/2] clipped to the head's row (stride 1, same length).
@@ -212,7 +222,7 @@ ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype) {
 
 void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float *part_m,
                         const float *part_l, float *lse, hipStream_t s) {
-  ADAKV_LAUNCH("score_lse_combine", lse_combine_kernel, dim3((RQ + 255) / 256, st.batch),
+  ADAKV_LAUNCH("score_lse_combine", lse_combine_kernel, dim3((RQ + 3) / 4, st.batch),
                dim3(256), s, st, ct, RQ, part_m, part_l, lse);
 }
 

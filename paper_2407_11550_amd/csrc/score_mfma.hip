@@ -40,6 +40,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TILE = 32;           // keys per MFMA tile
+#ifndef ADAKV_CHUNK_SWITCH_WGS
+#define ADAKV_CHUNK_SWITCH_WGS 512
+#endif
+constexpr long long CHUNK_SWITCH_WGS = ADAKV_CHUNK_SWITCH_WGS;   // fewer workgroups than this: halve the chunk
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -88,6 +92,70 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   const int row0 = rs * RW;                  // first window row of this wavefront
   const size_t head_row0 = (size_t)b * RQ + (size_t)c * R;
 
+  // ---- K path ---------------------------------------------------------------------------------
+  // An iteration covers KG consecutive tiles (one per wavefront group).  All threads of the
+  // workgroup load the iteration's rows together: 16 lanes per 256-byte row, every byte read
+  // once per workgroup, addressed as a wave-uniform 64-bit base (scalar registers) plus a
+  // 32-bit per-lane offset.  The loads of iterations it+1 and it+2 are in flight while
+  // iteration it is computed (two register sets, two LDS buffers, one barrier per iteration).
+  constexpr int TW = TILE * ROW16;                     // 16-byte words per tile
+  constexpr int LDPT = KG * TW / NT;                   // loads per thread per iteration
+  static_assert(KG * TW % NT == 0 && LDPT >= 1, "tile set must split evenly over the threads");
+  const char *kbase = reinterpret_cast<const char *>(K) +
+                      ((size_t)st.tok_off[b] * dm.k_stride_tok + (size_t)c * dm.k_stride_head) * 2;
+  const size_t tok_bytes = (size_t)dm.k_stride_tok * 2;
+  // word tid + i*NT of the iteration's KG*TW words: row (relative to the iteration's first key)
+  // and 16-byte column
+  int ld_rel[LDPT];
+  int wr_off[LDPT];                                    // word offset in an LDS buffer
+  const unsigned col_bytes = (unsigned)(tid % ROW16) * 16u;
+#pragma unroll
+  for (int i = 0; i < LDPT; ++i) {
+    const int wi = tid + i * NT;
+    const int tl = wi / TW, row = (wi % TW) / ROW16;
+    ld_rel[i] = tl * TILE + row;
+    wr_off[i] = tl * (TILE * STRIDE16) + row * STRIDE16 + tid % ROW16;
+  }
+  const int rd_off = kg * (TILE * STRIDE16) + l32 * STRIDE16 + half;
+  const int iters = (ntiles + KG - 1) / KG;
+  // The workgroups of a head run side by side and their chunks lie a fixed power-of-two number
+  // of bytes apart; if all of them walked their chunk from its first row, they would ask for
+  // addresses that are equal modulo that distance at the same time, i.e. the same memory
+  // channels.  Each workgroup therefore starts at a different point of its chunk and wraps
+  // around (neither sweep depends on the order of the tiles).
+  const int rot = (int)(((long long)chunk * iters) / (ct.off[b + 1] - ct.off[b]));
+  auto phys = [&](int it) { const int p = it + rot; return p >= iters ? p - iters : p; };
+
+  // Branch-free on purpose (the compiler can only keep older loads in flight across a wait if
+  // the loads in between are issued on every path).  Rows are clamped into the range somebody
+  // reads: past the end of the sequence they re-read row n-1 (masked out later), and of the two
+  // halo tiles only the pool radius next to the chunk is fetched, the other rows repeat the
+  // nearest needed one (a cache hit) and their results are never looked at.
+  // tok_bytes < 2^24 is checked on the host.
+  const int pool_r = (PASS == 2 && halo) ? dm.pool_k / 2 : 0;
+  const int need_lo = max(kc0 - pool_r, 0), need_hi = min(kc1 - 1 + pool_r, n - 1);
+  auto load_set = [&](u32x4 (&g)[LDPT], int it) {
+    const int key0 = k0 + it * KG * TILE;              // first key of the iteration
+    const int lim = need_hi - key0, lo = need_lo - key0;
+    const char *sb = kbase + (size_t)key0 * tok_bytes;
+#pragma unroll
+    for (int i = 0; i < LDPT; ++i) {
+      const unsigned off =
+          __umul24((unsigned)max(min(ld_rel[i], lim), lo), (unsigned)tok_bytes) + col_bytes;
+      g[i] = *reinterpret_cast<const u32x4 *>(sb + off);
+    }
+  };
+  auto store_set = [&](const u32x4 (&g)[LDPT], int buf) {
+#pragma unroll
+    for (int i = 0; i < LDPT; ++i) kt[buf][wr_off[i]] = g[i];
+  };
+
+  // The first two tile sets are requested before anything else is, so that the query
+  // fragments and the log-sum-exp rows below are fetched in the shadow of that round trip.
+  u32x4 g0[LDPT], g1[LDPT];
+  load_set(g0, phys(0));
+  load_set(g1, phys(min(1, iters - 1)));
+
   // ---- window queries of this wavefront as MFMA operands, kept for the whole chunk ----------
   // (rows past R are loaded from row R-1 and zeroed, so every load is unconditional)
   bf16x8 qf[MB][KS];
@@ -118,13 +186,27 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
       const int qi = tid % RPAD, sl = tid / RPAD;
       float M = -INFINITY, L = 0.0f;
       if (qi < R) {
-        for (int k = ct.off[b] + sl; k < ct.off[b + 1]; k += SL) {
-          const size_t o = (size_t)k * RQ + (size_t)c * R + qi;
-          const float m = part_m[o] * LOG2E, l = part_l[o];
-          const float nm = fmaxf(M, m);
-          const float ref = (nm == -INFINITY) ? 0.0f : nm;
-          L = L * fast_exp2(M - ref) + l * fast_exp2(m - ref);
-          M = nm;
+        // eight chunks' partials are loaded at a time (one round trip), then folded in
+        const int kend = ct.off[b + 1];
+        for (int k0c = ct.off[b] + sl; k0c < kend; k0c += 8 * SL) {
+          float pm[8], pl[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int k = min(k0c + u * SL, kend - 1);
+            const size_t o = (size_t)k * RQ + (size_t)c * R + qi;
+            pm[u] = part_m[o];
+            pl[u] = part_l[o];
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            if (k0c + u * SL < kend) {
+              const float m = pm[u] * LOG2E;
+              const float nm = fmaxf(M, m);
+              const float ref = (nm == -INFINITY) ? 0.0f : nm;
+              L = L * fast_exp2(M - ref) + pl[u] * fast_exp2(m - ref);
+              M = nm;
+            }
+          }
         }
       }
       sh_cm[tid] = M;
@@ -153,106 +235,65 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) { rm[mb] = -INFINITY; rl[mb] = 0.0f; }
 
-  // ---- K path ---------------------------------------------------------------------------------
-  // An iteration covers KG consecutive tiles (one per wavefront group).  All threads of the
-  // workgroup load the iteration's rows together: 16 lanes per 256-byte row, every byte read
-  // once per workgroup, addressed as a wave-uniform 64-bit base (scalar registers) plus a
-  // 32-bit per-lane offset.  The loads of iterations it+1, it+2 and it+3 are in flight while
-  // iteration it is computed (three register sets, two LDS buffers, one barrier per iteration).
-  constexpr int TW = TILE * ROW16;                     // 16-byte words per tile
-  constexpr int LDPT = KG * TW / NT;                   // loads per thread per iteration
-  static_assert(KG * TW % NT == 0 && LDPT >= 1, "tile set must split evenly over the threads");
-  const char *kbase = reinterpret_cast<const char *>(K) +
-                      ((size_t)st.tok_off[b] * dm.k_stride_tok + (size_t)c * dm.k_stride_head) * 2;
-  const size_t tok_bytes = (size_t)dm.k_stride_tok * 2;
-  // word tid + i*NT of the iteration's KG*TW words: row (relative to the iteration's first key)
-  // and 16-byte column
-  int ld_rel[LDPT];
-  int wr_off[LDPT];                                    // word offset in an LDS buffer
-  const unsigned col_bytes = (unsigned)(tid % ROW16) * 16u;
-#pragma unroll
-  for (int i = 0; i < LDPT; ++i) {
-    const int wi = tid + i * NT;
-    const int tl = wi / TW, row = (wi % TW) / ROW16;
-    ld_rel[i] = tl * TILE + row;
-    wr_off[i] = tl * (TILE * STRIDE16) + row * STRIDE16 + tid % ROW16;
-  }
-  const int rd_off = kg * (TILE * STRIDE16) + l32 * STRIDE16 + half;
-  const int iters = (ntiles + KG - 1) / KG;
-  // The workgroups of a head run side by side and their chunks lie a fixed power-of-two number
-  // of bytes apart; if all of them walked their chunk from its first row, they would ask for
-  // addresses that are equal modulo that distance at the same time, i.e. the same memory
-  // channels.  Each workgroup therefore starts at a different point of its chunk and wraps
-  // around (neither sweep depends on the order of the tiles).
-  const int rot = (int)(((long long)chunk * iters) / (ct.off[b + 1] - ct.off[b]));
-  auto phys = [&](int it) { const int p = it + rot; return p >= iters ? p - iters : p; };
 
-  // Branch-free on purpose (the compiler can only keep older loads in flight across a wait if
-  // the loads in between are issued on every path): rows past the end of the sequence re-read
-  // row n-1 and are masked out later.  tok_bytes < 2^24 is checked on the host.
-  auto load_set = [&](u32x4 (&g)[LDPT], int it) {
-    const int key0 = k0 + it * KG * TILE;              // first key of the iteration
-    const int lim = n - 1 - key0;
-    const char *sb = kbase + (size_t)key0 * tok_bytes;
+  // The matrix products of a tile and the softmax arithmetic on the PREVIOUS tile's products are
+  // independent, so they are written back to back in one basic block: the scheduler interleaves
+  // them and the exponentials of tile t run in the shadow of the MFMAs of tile t+1 (within one
+  // wavefront, not only between the two wavefronts of a SIMD).
+  auto mma = [&](const bf16x8 (&kf)[KS], floatx16 (&acc)[MB]) {
 #pragma unroll
-    for (int i = 0; i < LDPT; ++i) {
-      const unsigned off = __umul24((unsigned)min(ld_rel[i], lim), (unsigned)tok_bytes) + col_bytes;
-      g[i] = *reinterpret_cast<const u32x4 *>(sb + off);
+    for (int mb = 0; mb < MB; ++mb) {
+      floatx16 a = {0};
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        a = PASS == 1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[mb][s], a, 0, 0, 0)
+                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mb][s], kf[s], a, 0, 0, 0);
+      acc[mb] = a;
     }
   };
-  auto store_set = [&](const u32x4 (&g)[LDPT], int buf) {
-#pragma unroll
-    for (int i = 0; i < LDPT; ++i) kt[buf][wr_off[i]] = g[i];
-  };
-
-  // one 32-key tile against this wavefront's rows; RAGGED masks keys at or past n
-  auto compute = [&](auto ragged_tag, const bf16x8 (&kf)[KS], int tile) {
+  // softmax arithmetic of one finished tile; RAGGED masks keys at or past n
+  auto epilogue = [&](auto ragged_tag, floatx16 (&acc)[MB], int tile) {
     constexpr bool RAGGED = decltype(ragged_tag)::value;
     const int base = k0 + tile * TILE;
     if (PASS == 1) {
+      // acc[mb][r]: key base + 8*(r/4) + 4*half + r%4, window row row0 + mb*32 + l32
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        floatx16 acc = {0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[mb][s], acc, 0, 0, 0);
-        // acc[r]: key base + 8*(r/4) + 4*half + r%4, window row row0 + mb*32 + l32
         if (RAGGED) {
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (base + 8 * (r / 4) + 4 * half + (r % 4) >= n) acc[r] = -INFINITY;
+            if (base + 8 * (r / 4) + 4 * half + (r % 4) >= n) acc[mb][r] = -INFINITY;
         }
-        float tm = acc[0];
+        float tm = acc[mb][0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[r]);
+        for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[mb][r]);
         const float nm = fmaxf(rm[mb], tm * c_log2);
         const float ref = (nm == -INFINITY) ? 0.0f : nm;
         float sum = 0.0f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c_log2, -ref));
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[mb][r], c_log2, -ref));
         rl[mb] = rl[mb] * fast_exp2(rm[mb] - ref) + sum;
         rm[mb] = nm;
       }
     } else {
+      // acc[mb][r]: window row row0 + mb*32 + 8*(r/4) + 4*half + r%4, key base + l32
       float sum = 0.0f;
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        floatx16 acc = {0};
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int s = 0; s < KS; ++s)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mb][s], kf[s], acc, 0, 0, 0);
-        // acc[r]: window row row0 + mb*32 + 8*(r/4) + 4*half + r%4, key base + l32
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c_log2, -l2[mb][r]));
-      }
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[mb][r], c_log2, -l2[mb][r]));
       sum += __shfl_xor(sum, 32);
       // keys past n in a ragged tile get a value nobody reads
       if (half == 0) sh_part[rs][tile * TILE + l32] = sum;   // key k0 + tile*TILE + l32
     }
   };
+  auto is_full = [&](int tile) { return k0 + tile * TILE + TILE <= n; };
 
-  // iteration it: LDS buffer it%2 holds its tiles; register sets gb and gc are in flight with the
-  // loads of it+1 and it+2; set ga is free and takes it+3's
+  floatx16 accp[MB];                                   // products of the tile before the current one
+  int prev_tile = -1;                                  // -1: none pending
+
+  // iteration it: LDS buffer it%2 holds its tiles; register set gb is in flight with the loads of
+  // it+1; set ga is free and takes it+2's
   auto step = [&](int it, u32x4 (&ga)[LDPT], u32x4 (&gb)[LDPT]) {
     bf16x8 kf[KS];
     const u32x4 *buf = kt[it & 1];
@@ -260,26 +301,41 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     for (int s = 0; s < KS; ++s) kf[s] = as_bf16(buf[rd_off + s * 2]);
     // always issued (the last iterations re-read the final set): a conditional load would make
     // the compiler wait for every outstanding load before the stores below
-    load_set(ga, phys(min(it + 3, iters - 1)));
+    load_set(ga, phys(min(it + 2, iters - 1)));
     const int tile = phys(it) * KG + kg;
-    if (tile < ntiles) {
-      if (k0 + tile * TILE + TILE <= n) compute(std::false_type{}, kf, tile);
-      else compute(std::true_type{}, kf, tile);
+    const bool have = tile < ntiles;
+    if (have && prev_tile >= 0 && is_full(prev_tile)) {
+      // the common case, straight-line: products of this tile, arithmetic of the previous one
+      floatx16 accn[MB];
+      mma(kf, accn);
+      epilogue(std::false_type{}, accp, prev_tile);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) accp[mb] = accn[mb];
+      prev_tile = tile;
+    } else {
+      if (prev_tile >= 0) {
+        if (is_full(prev_tile)) epilogue(std::false_type{}, accp, prev_tile);
+        else epilogue(std::true_type{}, accp, prev_tile);
+      }
+      prev_tile = -1;
+      if (have) {
+        mma(kf, accp);
+        prev_tile = tile;
+      }
     }
     if (it + 1 < iters) store_set(gb, (it + 1) & 1);
     __syncthreads();
   };
   {
-    u32x4 g0[LDPT], g1[LDPT], g2[LDPT];
-    load_set(g0, phys(0));
-    load_set(g1, phys(min(1, iters - 1)));
-    load_set(g2, phys(min(2, iters - 1)));
     store_set(g0, 0);
     __syncthreads();
-    for (int it = 0; it < iters; it += 3) {
+    for (int it = 0; it < iters; it += 2) {
       step(it, g0, g1);
-      if (it + 1 < iters) step(it + 1, g1, g2);
-      if (it + 2 < iters) step(it + 2, g2, g0);
+      if (it + 1 < iters) step(it + 1, g1, g0);
+    }
+    if (prev_tile >= 0) {
+      if (is_full(prev_tile)) epilogue(std::false_type{}, accp, prev_tile);
+      else epilogue(std::true_type{}, accp, prev_tile);
     }
   }
 
@@ -374,7 +430,16 @@ void run_mfma_d(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   const int R = dm.g * dm.w;
   if (R <= 32) run_mfma<D, 1, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
   else if (R <= 64) run_mfma<D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else if (R <= 128) run_mfma<D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else if (R <= 128) {
+    // chunk length: long chunks amortise the per-workgroup set-up, but every compute unit wants
+    // a few workgroups to choose from
+    long long keys = 0;
+    for (int b = 0; b < st.batch; ++b) keys += st.n[b];
+    const long long wg2048 = (keys / 2048 + st.batch) * dm.h_kv;
+    if (wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
+    else if (2 * wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
+    else run_mfma<D, 2, 2, 2, 512>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  }
   else if (R <= 256) run_mfma<D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
   // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
   // a tile half the loads, so four wavefronts of 128 rows

@@ -219,13 +219,26 @@ def test_two_runs_are_bit_identical():
 
 
 # ------------------------------------------------------------------------------ full sizes
-@pytest.mark.parametrize("name", ["llama8b_32k", "llama8b_128k"])
-def test_full_size_layer(name):
-    _say(f"full size {name}")
-    wl = synth.workload(name)
+@pytest.mark.parametrize("name,alpha", [("llama8b_32k", None), ("llama8b_128k", None),
+                                        ("llama70b_128k", 0.2), ("llama70b_128k", 1.0)])
+def test_full_size_layer(name, alpha):
+    _say(f"full size {name} alpha {alpha}")
+    wl = synth.workload(name, alpha=alpha)
     q, K, V = synth.generate(wl, device=DEV)
     _, out = _run(wl, q, K, V)
     _say("  gpu done, oracle running")
     _check_all(wl, q, K, V, out)
     bud = out["budgets"].cpu().numpy()
     _say(f"  budgets min {bud.min()} max {bud.max()}")
+
+
+def test_full_size_ragged_batch_one_layer():
+    # batch 8, prefix lengths drawn from [4096, 65536], budgets 5 % of n per head, packed layout:
+    # one of the 32 layers of the ragged workload, every sequence compared in full
+    _say("full size ragged batch")
+    wl = synth.workload("llama8b_ragged")
+    q, K, V = synth.generate(wl, layer=3, device=DEV)
+    _, out = _run(wl, q, K, V)
+    _say(f"  gpu done, n = {wl.n}")
+    _check_all(wl, q, K, V, out)
+    assert int(out["cu_seqlens"][-1]) == sum(wl.B)
