@@ -72,18 +72,37 @@ struct Rank {
   int krem;          // rank of the threshold among the elements matching them; 0 = select nothing
 };
 
-// All 256 threads of a block: given the finished histogram of pass P (NB bins) and the rank
-// krem >= 1 among the elements it counts, find the digit whose bin holds that rank, counting
-// from the largest digit down.  Returns the digit and the rank inside its bin (>= 1).
+// This thread's NB/256 consecutive bins of a finished histogram, as 16-byte loads.  Kept apart
+// from locate() so that callers can issue these loads together with everything else they need
+// from memory (one round trip instead of a chain of them).
+template <int NB> struct Bins { unsigned v[NB / 256]; };
+template <int NB> __device__ __forceinline__ Bins<NB> load_bins(const unsigned *__restrict__ bins) {
+  constexpr int PER = NB / 256;
+  Bins<NB> r;
+  // threads past the first 256 of a wider block own no bins
+  const uint4 *p = reinterpret_cast<const uint4 *>(bins + (threadIdx.x & 255) * PER);
+  const unsigned keep = threadIdx.x < 256 ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+  for (int i = 0; i < PER / 4; ++i) {
+    const uint4 q = p[i];
+    r.v[4 * i] = q.x & keep; r.v[4 * i + 1] = q.y & keep;
+    r.v[4 * i + 2] = q.z & keep; r.v[4 * i + 3] = q.w & keep;
+  }
+  return r;
+}
+
+// All threads of a block (the first 256 hold the bins): given the finished histogram of a pass (NB bins, this thread's part
+// in `mine`) and the rank krem >= 1 among the elements it counts, find the digit whose bin holds
+// that rank, counting from the largest digit down.  Returns the digit and the rank inside its
+// bin (>= 1).
 template <int NB>
-__device__ __forceinline__ void locate(const unsigned *__restrict__ bins, int krem,
-                                       unsigned &digit, int &rank_in_bin, unsigned *sh /*[8]*/) {
+__device__ __forceinline__ void locate(const Bins<NB> &mine, int krem, unsigned &digit,
+                                       int &rank_in_bin, unsigned *sh /*[8]*/) {
   constexpr int PER = NB / 256;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  unsigned mine[PER];
   unsigned s = 0;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) { mine[i] = bins[tid * PER + i]; s += mine[i]; }
+  for (int i = 0; i < PER; ++i) s += mine.v[i];
   unsigned suf = s;                                    // sum over lanes >= this one
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -91,7 +110,7 @@ __device__ __forceinline__ void locate(const unsigned *__restrict__ bins, int kr
     if (lane + off < 64) suf += v;
   }
   __syncthreads();                                     // sh may be in use by the caller
-  if (lane == 0) sh[wv] = suf;
+  if (lane == 0 && wv < 4) sh[wv] = suf;
   if (tid == 0) { sh[4] = 0u; sh[5] = (unsigned)krem; }   // fallback keeps later reads in bounds
   __syncthreads();
   unsigned above = suf - s;                            // elements in bins owned by higher threads
@@ -100,11 +119,11 @@ __device__ __forceinline__ void locate(const unsigned *__restrict__ bins, int kr
     unsigned acc = above;
 #pragma unroll
     for (int i = PER - 1; i >= 0; --i) {
-      if (acc < (unsigned)krem && (unsigned)krem <= acc + mine[i]) {
+      if (acc < (unsigned)krem && (unsigned)krem <= acc + mine.v[i]) {
         sh[4] = (unsigned)(tid * PER + i);
         sh[5] = (unsigned)krem - acc;
       }
-      acc += mine[i];
+      acc += mine.v[i];
     }
   }
   __syncthreads();
@@ -129,25 +148,33 @@ __device__ __forceinline__ Rank rank_before_pass(const SeqTab &st, int h, int b,
   const int nsegs = st.batch * h;
   const int S = LAYER ? b : b * h + c;
   Rank r;
-  if (P <= 1) {
-    r.prefix = 0u;
+  r.prefix = 0u;
+  r.krem = 0;
+  if (P == 0) {
     r.krem = LAYER ? st.Bp[b] : budgets[b * h + c];
+    return r;
   } else {
-    const uint2 v = state[(size_t)(P - 2) * nsegs + S];
-    r.prefix = v.x;
-    r.krem = (int)v.y;
+    constexpr int Q = P - 1;                           // the pass whose histogram is scanned
+    constexpr int NBQ = (Q == 2) ? 1024 : RADIX_BINS;
+    const unsigned *bins = LAYER ? hist_tot + ((size_t)Q * st.batch + b) * RADIX_BINS
+                                 : hist + ((size_t)Q * nsegs + b * h + c) * RADIX_BINS;
+    // the histogram and the stored state do not depend on each other: both loads go out now
+    const Bins<NBQ> mine = load_bins<NBQ>(bins);
+    if (P == 1) {
+      r.krem = LAYER ? st.Bp[b] : budgets[b * h + c];
+    } else {
+      const uint2 v = state[(size_t)(P - 2) * nsegs + S];
+      r.prefix = v.x;
+      r.krem = (int)v.y;
+    }
+    if (r.krem <= 0) return r;
+    unsigned digit;
+    int rank;
+    locate<NBQ>(mine, r.krem, digit, rank, sh);
+    r.prefix = with_digit<Q>(r.prefix, digit);
+    r.krem = rank;
+    return r;
   }
-  if (P == 0 || r.krem <= 0) return r;
-  constexpr int Q = P - 1;                             // the pass whose histogram is scanned
-  constexpr int NBQ = (Q == 2) ? 1024 : RADIX_BINS;
-  const unsigned *bins = LAYER ? hist_tot + ((size_t)Q * st.batch + b) * RADIX_BINS
-                               : hist + ((size_t)Q * nsegs + b * h + c) * RADIX_BINS;
-  unsigned digit;
-  int rank;
-  locate<NBQ>(bins, r.krem, digit, rank, sh);
-  r.prefix = with_digit<Q>(r.prefix, digit);
-  r.krem = rank;
-  return r;
 }
 
 // One histogram pass.  grid.x runs over the SEL_CHUNK-sized chunks of all sequences, grid.y over
@@ -168,18 +195,25 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
   const int c = blockIdx.y;
   const int n = st.n[b];
   const int nsegs = st.batch * h;
+  // the block's scores are requested first, so they arrive while the prologue below waits for
+  // the previous pass's histogram (indices past the end are clamped, the values ignored)
+  const float *row = scores + st.score_off[b] + (size_t)c * n;
+  const int j0 = chunk * SEL_CHUNK;
+  const int j1 = min(n, j0 + SEL_CHUNK);
+  constexpr int EPB = SEL_CHUNK / 256;
+  float sc[EPB];
+#pragma unroll
+  for (int i = 0; i < EPB; ++i) sc[i] = row[min(j0 + tid + 256 * i, j1 - 1)];
   for (int i = tid; i < NB; i += 256) lh[i] = 0u;
   const Rank r = rank_before_pass<P, LAYER>(st, h, b, c, budgets, hist, hist_tot, state, sh);
   if (P >= 1 && chunk == 0 && (!LAYER || c == 0) && tid == 0)
     state[(size_t)(P - 1) * nsegs + (LAYER ? b : b * h + c)] = make_uint2(r.prefix, (unsigned)r.krem);
   __syncthreads();
   if (r.krem <= 0) return;                             // nothing to select in this segment
-  const float *row = scores + st.score_off[b] + (size_t)c * n;
-  const int j0 = chunk * SEL_CHUNK;
-  const int j1 = min(n, j0 + SEL_CHUNK);
-  for (int j = j0 + tid; j < j1; j += 256) {
-    const unsigned key = key_of(row[j]);
-    if (matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
+#pragma unroll
+  for (int i = 0; i < EPB; ++i) {
+    const unsigned key = key_of(sc[i]);
+    if (j0 + tid + 256 * i < j1 && matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
   }
   __syncthreads();
   unsigned *gh = hist + ((size_t)P * nsegs + b * h + c) * RADIX_BINS;
@@ -203,34 +237,41 @@ __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int
                                                            int *__restrict__ cu) {
   __shared__ unsigned sh[8];
   __shared__ int sh_gt[64], sh_eq[64];
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int b = blockIdx.x;
   const int nsegs = st.batch * h;
   if (tid < 64) { sh_gt[tid] = 0; sh_eq[tid] = 0; }
+  // Wavefront wv takes heads wv, wv+4, ...; a lane loads all its bins of the three histograms
+  // of a head at once (20 independent 16-byte loads).  The first head's loads are issued before
+  // the threshold is known (they do not depend on it), so they share its round trip.
+  struct HeadBins { uint4 v0[8], v1[8], v2[4]; };
+  auto load_head = [&](int c) {
+    HeadBins hb;
+    const int cc = min(c, h - 1);
+    const uint4 *b0 = reinterpret_cast<const uint4 *>(hist + ((size_t)0 * nsegs + b * h + cc) * RADIX_BINS) + lane * 8;
+    const uint4 *b1 = reinterpret_cast<const uint4 *>(hist + ((size_t)1 * nsegs + b * h + cc) * RADIX_BINS) + lane * 8;
+    const uint4 *b2 = reinterpret_cast<const uint4 *>(hist + ((size_t)2 * nsegs + b * h + cc) * RADIX_BINS) + lane * 4;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { hb.v0[i] = b0[i]; hb.v1[i] = b1[i]; }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) hb.v2[i] = b2[i];
+    return hb;
+  };
+  HeadBins first = load_head(wv);
   const Rank r = rank_before_pass<3, true>(st, h, b, 0, nullptr, hist, hist_tot, state, sh);
   __syncthreads();
   // r.prefix is the threshold key, r.krem how many threshold-valued elements are taken (in
   // flat-index order, i.e. head by head).  Per head: elements strictly above the threshold are
   // those in higher bins of pass 0, plus higher bins of pass 1 under the same first digit, ...
-  // Wavefront wv takes heads wv, wv+4, ...; a lane loads all its bins of the three histograms
-  // of a head at once (20 independent 16-byte loads), so a head costs one memory round trip.
   if (r.krem > 0) {
     const unsigned d0 = digit_of<0>(r.prefix), d1 = digit_of<1>(r.prefix), d2 = digit_of<2>(r.prefix);
-    const int lane = tid & 63, wv = tid >> 6;
     for (int c = wv; c < h; c += 4) {
-      const uint4 *b0 = reinterpret_cast<const uint4 *>(hist + ((size_t)0 * nsegs + b * h + c) * RADIX_BINS) + lane * 8;
-      const uint4 *b1 = reinterpret_cast<const uint4 *>(hist + ((size_t)1 * nsegs + b * h + c) * RADIX_BINS) + lane * 8;
-      const uint4 *b2 = reinterpret_cast<const uint4 *>(hist + ((size_t)2 * nsegs + b * h + c) * RADIX_BINS) + lane * 4;
-      uint4 v0[8], v1[8], v2[4];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) { v0[i] = b0[i]; v1[i] = b1[i]; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) v2[i] = b2[i];
+      const HeadBins hb = (c == wv) ? first : load_head(c);
       int cnt = 0, eq = 0;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const unsigned a0[4] = {v0[i].x, v0[i].y, v0[i].z, v0[i].w};
-        const unsigned a1[4] = {v1[i].x, v1[i].y, v1[i].z, v1[i].w};
+        const unsigned a0[4] = {hb.v0[i].x, hb.v0[i].y, hb.v0[i].z, hb.v0[i].w};
+        const unsigned a1[4] = {hb.v1[i].x, hb.v1[i].y, hb.v1[i].z, hb.v1[i].w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const unsigned bin = (unsigned)(lane * 32 + i * 4 + k);
@@ -240,7 +281,7 @@ __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const unsigned a2[4] = {v2[i].x, v2[i].y, v2[i].z, v2[i].w};
+        const unsigned a2[4] = {hb.v2[i].x, hb.v2[i].y, hb.v2[i].z, hb.v2[i].w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const unsigned bin = (unsigned)(lane * 16 + i * 4 + k);
@@ -262,7 +303,7 @@ __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int
   const int c = tid;
   const bool live = c < h;
   const long long Bp = st.Bp[b];
-  const long long one = 65536, a = alpha_fix, den = one * h;
+  const long long one = 65536, a = alpha_fix;
   long long rem = -1;
   int base = 0;
   if (live) {
@@ -272,9 +313,13 @@ __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int
     if (avail < 0) avail = 0;
     const long long take = sh_eq[c] < avail ? sh_eq[c] : avail;
     const long long f = (long long)sh_gt[c] + take;     // Algorithm 1: B*_c = f_c
-    const long long num = (one - a) * h * f + a * Bp;   // x_c = num / den
-    base = (int)(num / den);
-    rem = num - (long long)base * den;
+    const long long num = (one - a) * h * f + a * Bp;   // x_c = num / den, den = 65536 h
+    // num / 65536 = (1-alpha) h f + alpha B' <= h f + B' < 2^32 (both sums are below 2^31), so
+    // the division by den is a shift and one 32-bit division; the remainders recombine exactly
+    const unsigned t = (unsigned)(num >> 16);
+    const unsigned tq = t / (unsigned)h, tr = t - tq * (unsigned)h;
+    base = (int)tq;
+    rem = ((long long)tr << 16) | (num & 0xFFFF);
   }
   sh_rem[c] = rem;
   sh_base[c] = base;
