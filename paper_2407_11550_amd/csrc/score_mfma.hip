@@ -399,12 +399,12 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   float *part_m = (float *)(ws + pl.part_m), *part_l = (float *)(ws + pl.part_l);
   float *lse = (float *)(ws + pl.lse), *raw = (float *)(ws + pl.raw);
   const dim3 block(64 * RS * KG);
-  // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a sequence has so
-  // many chunks that every workgroup re-reading them would cost more than a kernel, and it
+  // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a head has so many
+  // (chunks x rows) that every workgroup re-reading them would cost more than a kernel, and it
   // applies the max-pool itself when the pool radius fits into the one-tile halo.
   int max_chunks = 0;
   for (int b = 0; b < st.batch; ++b) max_chunks = ct.off[b + 1] - ct.off[b] > max_chunks ? ct.off[b + 1] - ct.off[b] : max_chunks;
-  const bool fuse_lse = max_chunks <= 128;
+  const bool fuse_lse = (long long)max_chunks * dm.g * dm.w <= 8192;
   const bool fuse_pool = dm.pool_k / 2 <= TILE;
   const float *use_lse = row_lse;
   if (!row_lse) {
