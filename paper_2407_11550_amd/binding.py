@@ -245,6 +245,13 @@ class KernelTrace:
         self.names = self.names[:self.used]
         return False
 
+    def marker_gaps_us(self):
+        """Microseconds between the marker at the end of one call and the marker in front of the
+        next call's first kernel: no kernel runs in between, so this is what the markers
+        themselves cost on the stream; call after a synchronize."""
+        return [1000.0 * self.events[i].elapsed_time(self.events[i + 1])
+                for i in range(self.used - 1) if self.names[i] == "end"]
+
     def durations_us(self):
         """[(kernel name, microseconds)] for every bracketed kernel; call after a synchronize."""
         out = []
