@@ -242,3 +242,20 @@ def test_full_size_ragged_batch_one_layer():
     _say(f"  gpu done, n = {wl.n}")
     _check_all(wl, q, K, V, out)
     assert int(out["cu_seqlens"][-1]) == sum(wl.B)
+
+
+def test_kernel_trace_names_every_kernel_and_costs_nothing_when_disarmed():
+    _say("kernel trace")
+    wl = synth.small_workload(8, 2, 128, 32, 7, 5000, 2 * 300, seed=3)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl)
+    ref = adakv.compress(layer, q, K, V)
+    with adakv.KernelTrace(64) as tr:
+        out = adakv.compress(layer, q, K, V)
+    torch.cuda.synchronize()
+    names = [n for n, _ in tr.durations_us()]
+    assert names[0].startswith("score_") and names[-1] == "compact"
+    assert sum(n.startswith("alloc_") for n in names) >= 4 and sum(n.startswith("select_") for n in names) >= 5
+    assert all(us >= 0 for _, us in tr.durations_us()) and len(tr.marker_gaps_us()) == 3
+    for key in ref:
+        assert torch.equal(ref[key], out[key]), key

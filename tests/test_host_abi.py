@@ -86,3 +86,37 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libadakv.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+
+
+def test_trace_arm_rejects_bad_arguments(lib):
+    assert lib.adakv_trace_arm(None, 4) == -1
+    arr = (ctypes.c_void_p * 2)()
+    assert lib.adakv_trace_arm(arr, 0) == -1 and lib.adakv_trace_arm(arr, 100000) == -1
+    assert lib.adakv_trace_disarm() == 0
+
+
+def test_generator_is_deterministic_and_shaped():
+    from paper_2407_11550_amd import synth
+    wl = synth.small_workload(8, 2, 128, 16, 7, [300, 77], [2 * 40, 2 * 20], seed=5)
+    a = synth.generate(wl)
+    b = synth.generate(wl)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    q, K, V = a
+    assert q.shape == (2, 8, 16, 128) and K.shape == (300 + 16 + 77 + 16, 2, 128) and V.shape == K.shape
+    assert wl.tok_off == [0, 316, 409]
+    c = synth.generate(wl, layer=1)
+    assert not torch.equal(c[1], K)                      # another layer, other values
+    names = ["tiny", "llama8b_32k", "llama8b_128k", "llama8b_ragged", "llama70b_128k"]
+    for nm in names:
+        w = synth.workload(nm)
+        for nb, Bb in zip(w.n, w.B):
+            assert w.w * w.h_kv <= Bb <= w.w * w.h_kv + w.h_kv * nb
