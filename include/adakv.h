@@ -160,6 +160,74 @@ int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int3
                   const int32_t *cu_seqlens, void *K_out, void *V_out, void *hip_stream);
 
 /*
+ * ---- Decode side of the flattened layout (Section 3.5; Section 3.1, Eqs. 1-2) --------------
+ *
+ * After compression every (sequence, KV head) segment s = b*h_kv + c has its own length.  The
+ * decode-side cache keeps the flattened layout and leaves `headroom` spare rows behind every
+ * segment for the tokens generated afterwards:
+ *
+ *     start_s = cu_seqlens[s] + s*headroom      first row of segment s in K_cache / V_cache
+ *     cap_s   = cu_seqlens[s+1] - cu_seqlens[s] + headroom
+ *     seg_len[s]                                rows currently held, device resident
+ *
+ * cu_seqlens stays as adakv_allocate wrote it for the whole life of the cache; only seg_len
+ * changes.  K_cache and V_cache are [sum_b B_b + batch*h_kv*headroom][d], contiguous, L->dtype,
+ * 16-byte aligned.  0 <= headroom, and the row count must stay below 2^31.
+ * Of L these calls use dtype, h_q, h_kv, d, w, batch, n, B, scale (B only to size the cache).
+ */
+
+/*
+ * adakv_compact with the head-room layout: for segment s = (b, c) and 0 <= t < cu[s+1]-cu[s]
+ *     K_cache[start_s + t][:] = K[tok_off[b] + indices[cu[s] + t]][c][:],   V_cache likewise,
+ * and seg_len[s] = cu[s+1] - cu[s].  Spare rows are not written.
+ *
+ *   K, V, indices, cu_seqlens   as for adakv_compact
+ *   seg_len (device) [batch*h_kv] int32, written
+ */
+int adakv_cache_build(const adakv_layer *L, const void *K, const void *V, const int32_t *indices,
+                      const int32_t *cu_seqlens, int32_t headroom, void *K_cache, void *V_cache,
+                      int32_t *seg_len, void *hip_stream);
+
+/*
+ * The cache update of Eq. (1), K_i = Cat[K_i : k_i] and V_i likewise, for every segment at
+ * once: row k_new[b][c] is stored at start_s + seg_len[s] and seg_len[s] grows by one.  A
+ * segment that is already full (seg_len[s] == cap_s) is left as it is and *overflow is set
+ * to 1 (it is never cleared by the library).
+ *
+ *   k_new, v_new (device) [batch][h_kv][d] contiguous, L->dtype, 16-byte aligned
+ *   seg_len      (device) [batch*h_kv] int32, read and written
+ *   overflow     (device) one int32, or NULL
+ */
+int adakv_append(const adakv_layer *L, const void *k_new, const void *v_new,
+                 const int32_t *cu_seqlens, int32_t headroom, void *K_cache, void *V_cache,
+                 int32_t *seg_len, int32_t *overflow, void *hip_stream);
+
+/* Scratch bytes adakv_decode_attn needs for this layer and head-room (0 on invalid input). */
+size_t adakv_decode_workspace_bytes(const adakv_layer *L, int32_t headroom);
+
+/*
+ * One decoding step of Eq. (2) per query head over segments of different lengths (the
+ * variable-length attention of Section 3.5): for sequence b and query head i, with
+ * s = b*h_kv + i/g and the seg_len[s] rows of that segment,
+ *
+ *     out[b][i][:] = sum_t softmax_t(scale * q_new[b][i] . K_cache[start_s + t]) V_cache[start_s + t][:]
+ *     lse[b][i]    = ln sum_t exp(scale * q_new[b][i] . K_cache[start_s + t])
+ *
+ * Logits, the softmax and the weighted sum are accumulated in fp32.  A segment of length 0
+ * gives a zero row and lse = -inf.  The projection by W^O is not part of this call.
+ *
+ *   q_new (device) [batch][h_q][d] contiguous, L->dtype, 16-byte aligned
+ *   out   (device) [batch][h_q][d] fp32, written
+ *   lse   (device) [batch][h_q] fp32, written; may be NULL
+ *   ws    (device) adakv_decode_workspace_bytes(L, headroom) bytes
+ * Supported (else ADAKV_EUNSUPPORTED): g = h_q/h_kv in {1, 2, 4, 8}; d in {64, 128}.
+ */
+int adakv_decode_attn(const adakv_layer *L, const void *q_new, const int32_t *cu_seqlens,
+                      int32_t headroom, const void *K_cache, const void *V_cache,
+                      const int32_t *seg_len, float *out, float *lse, void *ws, size_t ws_bytes,
+                      void *hip_stream);
+
+/*
  * Profiling aid for benchmarks (no part of the method).  While armed, on the arming host thread,
  * the library records the caller's events, in order, on the call's stream: one in front of every
  * kernel it launches and one at the end of every ABI call, until the array is used up.  Event i

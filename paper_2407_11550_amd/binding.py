@@ -65,6 +65,15 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = args
+    I = ctypes.c_int32
+    for name, args in (("adakv_cache_build", [P, V, V, V, V, I, V, V, V, V]),
+                       ("adakv_append", [P, V, V, V, I, V, V, V, V, V]),
+                       ("adakv_decode_attn", [P, V, V, I, V, V, V, V, V, V, Z, V])):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = args
+    lib.adakv_decode_workspace_bytes.restype = Z
+    lib.adakv_decode_workspace_bytes.argtypes = [P, I]
     lib.adakv_trace_arm.restype = ctypes.c_int
     lib.adakv_trace_arm.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
     lib.adakv_trace_disarm.restype = ctypes.c_int
@@ -218,6 +227,93 @@ def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, b
     idx = select(layer, sc, bud, cu, b.get("indices"), ws=ws, stream=stream)
     K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
     return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
+
+
+# ---- decode side of the flattened layout ---------------------------------------------------------
+def cache_rows(layer: Layer, headroom: int) -> int:
+    """Rows of K_cache / V_cache: every segment's retained rows plus `headroom` spare rows each."""
+    return layer.num_rows_out + layer.num_segments * int(headroom)
+
+
+def decode_workspace_bytes(layer: Layer, headroom: int) -> int:
+    return int(load_library().adakv_decode_workspace_bytes(ctypes.byref(layer.c), int(headroom)))
+
+
+def cache_build(layer: Layer, K, V, indices, cu_seqlens, headroom, K_cache=None, V_cache=None,
+                seg_len=None, stream=None):
+    """adakv_cache_build: the gather of adakv_compact into the layout with head-room; returns
+    (K_cache, V_cache, seg_len)."""
+    lib = load_library()
+    rows = cache_rows(layer, headroom)
+    if K_cache is None:
+        K_cache = torch.empty((rows, layer.d), dtype=layer.torch_dtype, device=K.device)
+    if V_cache is None:
+        V_cache = torch.empty((rows, layer.d), dtype=layer.torch_dtype, device=K.device)
+    if seg_len is None:
+        seg_len = torch.empty(layer.num_segments, dtype=torch.int32, device=K.device)
+    if K_cache.shape[0] < rows or V_cache.shape[0] < rows or seg_len.numel() < layer.num_segments:
+        raise ValueError("cache or seg_len too small for this layer and head-room")
+    st = lib.adakv_cache_build(ctypes.byref(layer.c), _ptr(K, "K", layer.torch_dtype),
+                               _ptr(V, "V", layer.torch_dtype), _ptr(indices, "indices", torch.int32),
+                               _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(headroom),
+                               _ptr(K_cache, "K_cache", layer.torch_dtype),
+                               _ptr(V_cache, "V_cache", layer.torch_dtype),
+                               _ptr(seg_len, "seg_len", torch.int32), _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_cache_build")
+    return K_cache, V_cache, seg_len
+
+
+def append(layer: Layer, k_new, v_new, cu_seqlens, headroom, K_cache, V_cache, seg_len,
+           overflow=None, stream=None):
+    """adakv_append: one new K/V row per (sequence, KV head) behind each segment; seg_len grows."""
+    lib = load_library()
+    want = (layer.batch, layer.h_kv, layer.d)
+    if tuple(k_new.shape) != want or tuple(v_new.shape) != want:
+        raise ValueError(f"k_new and v_new must be {want}")
+    if not (k_new.is_contiguous() and v_new.is_contiguous()):
+        raise ValueError("k_new and v_new must be contiguous")
+    if K_cache.shape[0] < cache_rows(layer, headroom) or V_cache.shape[0] < cache_rows(layer, headroom):
+        raise ValueError("cache too small for this layer and head-room")
+    st = lib.adakv_append(ctypes.byref(layer.c), _ptr(k_new, "k_new", layer.torch_dtype),
+                          _ptr(v_new, "v_new", layer.torch_dtype),
+                          _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(headroom),
+                          _ptr(K_cache, "K_cache", layer.torch_dtype),
+                          _ptr(V_cache, "V_cache", layer.torch_dtype),
+                          _ptr(seg_len, "seg_len", torch.int32),
+                          _ptr(overflow, "overflow", torch.int32), _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_append")
+    return seg_len
+
+
+def decode_attn(layer: Layer, q_new, cu_seqlens, headroom, K_cache, V_cache, seg_len, out=None,
+                lse=None, ws=None, stream=None, want_lse=False):
+    """adakv_decode_attn: out [batch, h_q, d] fp32 (and lse [batch, h_q] if asked for)."""
+    lib = load_library()
+    want = (layer.batch, layer.h_q, layer.d)
+    if tuple(q_new.shape) != want or not q_new.is_contiguous():
+        raise ValueError(f"q_new must be contiguous {want}")
+    if K_cache.shape[0] < cache_rows(layer, headroom) or V_cache.shape[0] < cache_rows(layer, headroom):
+        raise ValueError("cache too small for this layer and head-room")
+    if out is None:
+        out = torch.empty(want, dtype=torch.float32, device=q_new.device)
+    if lse is None and want_lse:
+        lse = torch.empty(want[:2], dtype=torch.float32, device=q_new.device)
+    if ws is None:
+        ws = torch.empty(max(decode_workspace_bytes(layer, headroom), 16), dtype=torch.uint8,
+                         device=q_new.device)
+    st = lib.adakv_decode_attn(ctypes.byref(layer.c), _ptr(q_new, "q_new", layer.torch_dtype),
+                               _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(headroom),
+                               _ptr(K_cache, "K_cache", layer.torch_dtype),
+                               _ptr(V_cache, "V_cache", layer.torch_dtype),
+                               _ptr(seg_len, "seg_len", torch.int32),
+                               _ptr(out, "out", torch.float32), _ptr(lse, "lse", torch.float32),
+                               ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel()),
+                               _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_decode_attn")
+    return (out, lse) if (want_lse or lse is not None) else out
 
 
 class KernelTrace:

@@ -179,8 +179,73 @@ int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int3
   if (!K || !V || !indices || !cu_seqlens || !K_out || !V_out) return ADAKV_EINVAL;
   if (!aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out))
     return ADAKV_EUNSUPPORTED;
-  hipError_t e = launch_compact(st, dm, L->dtype, K, V, indices, cu_seqlens, K_out, V_out,
-                                (hipStream_t)hip_stream);
+  hipError_t e = launch_compact(st, dm, L->dtype, K, V, indices, cu_seqlens, K_out, V_out, 0,
+                                nullptr, (hipStream_t)hip_stream);
+  trace_mark((hipStream_t)hip_stream, "end");
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+// ---- decode side ------------------------------------------------------------------------------
+static int check_headroom(const SeqTab &st, const Dims &dm, int32_t headroom) {
+  if (headroom < 0) return ADAKV_EINVAL;
+  const long long rows = (long long)st.out_off[st.batch] + (long long)st.batch * dm.h_kv * headroom;
+  return rows < (1ll << 31) ? ADAKV_OK : ADAKV_EUNSUPPORTED;
+}
+
+int adakv_cache_build(const adakv_layer *L, const void *K, const void *V, const int32_t *indices,
+                      const int32_t *cu_seqlens, int32_t headroom, void *K_cache, void *V_cache,
+                      int32_t *seg_len, void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if ((rc = check_headroom(st, dm, headroom)) != ADAKV_OK) return rc;
+  if (!K || !V || !indices || !cu_seqlens || !K_cache || !V_cache || !seg_len) return ADAKV_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(K_cache) || !aligned16(V_cache))
+    return ADAKV_EUNSUPPORTED;
+  hipError_t e = launch_compact(st, dm, L->dtype, K, V, indices, cu_seqlens, K_cache, V_cache,
+                                headroom, seg_len, (hipStream_t)hip_stream);
+  trace_mark((hipStream_t)hip_stream, "end");
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+int adakv_append(const adakv_layer *L, const void *k_new, const void *v_new,
+                 const int32_t *cu_seqlens, int32_t headroom, void *K_cache, void *V_cache,
+                 int32_t *seg_len, int32_t *overflow, void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if ((rc = check_headroom(st, dm, headroom)) != ADAKV_OK) return rc;
+  if (!k_new || !v_new || !cu_seqlens || !K_cache || !V_cache || !seg_len) return ADAKV_EINVAL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(K_cache) || !aligned16(V_cache))
+    return ADAKV_EUNSUPPORTED;
+  hipError_t e = launch_append(st, dm, L->dtype, headroom, k_new, v_new, cu_seqlens, K_cache,
+                               V_cache, seg_len, overflow, (hipStream_t)hip_stream);
+  trace_mark((hipStream_t)hip_stream, "end");
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+size_t adakv_decode_workspace_bytes(const adakv_layer *L, int32_t headroom) {
+  SeqTab st; Dims dm;
+  if (build_tables(L, st, dm) != ADAKV_OK || check_headroom(st, dm, headroom) != ADAKV_OK) return 0;
+  if (!decode_supported(dm)) return 0;
+  return plan_decode(st, dm, headroom).total + 256;
+}
+
+int adakv_decode_attn(const adakv_layer *L, const void *q_new, const int32_t *cu_seqlens,
+                      int32_t headroom, const void *K_cache, const void *V_cache,
+                      const int32_t *seg_len, float *out, float *lse, void *ws, size_t ws_bytes,
+                      void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if ((rc = check_headroom(st, dm, headroom)) != ADAKV_OK) return rc;
+  if (!q_new || !cu_seqlens || !K_cache || !V_cache || !seg_len || !out) return ADAKV_EINVAL;
+  if (!decode_supported(dm)) return ADAKV_EUNSUPPORTED;
+  if (!aligned16(q_new) || !aligned16(K_cache) || !aligned16(V_cache)) return ADAKV_EUNSUPPORTED;
+  if (!ws || ws_bytes < plan_decode(st, dm, headroom).total + 256) return ADAKV_EWORKSPACE;
+  char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
+  hipError_t e = launch_decode_attn(st, dm, L->dtype, headroom, q_new, cu_seqlens, K_cache,
+                                    V_cache, seg_len, out, lse, wsp, (hipStream_t)hip_stream);
   trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }

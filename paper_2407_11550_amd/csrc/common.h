@@ -40,6 +40,8 @@ __device__ __forceinline__ int find_seq(const ChunkTab &ct, int batch, int blk) 
   return b;
 }
 
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
 struct Dims {
   int h_q, h_kv, g, d, w, pool_k;
   float scale;      // logit scale actually applied
@@ -80,9 +82,24 @@ hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
 // ---- compaction (compact.hip) ---------------------------------------------------------------
 hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const void *K,
                           const void *V, const int *indices, const int *cu_seqlens, void *K_out,
-                          void *V_out, hipStream_t s);
+                          void *V_out, int headroom, int *seg_len, hipStream_t s);
 
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// ---- decode side of the flattened layout (decode.hip) -----------------------------------------
+struct DecodePlan {
+  int split;                        // rows of a segment per workgroup
+  int nblk;                         // workgroups launched: an upper bound on what the lengths need
+  size_t part_acc, part_ml, total;  // byte offsets of the per-workgroup partial results
+};
+bool decode_supported(const Dims &dm);
+DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom);
+hipError_t launch_decode_attn(const SeqTab &st, const Dims &dm, int dtype, int headroom,
+                              const void *q, const int *cu, const void *Kc, const void *Vc,
+                              const int *seg_len, float *out, float *lse, char *ws,
+                              hipStream_t s);
+hipError_t launch_append(const SeqTab &st, const Dims &dm, int dtype, int headroom,
+                         const void *k_new, const void *v_new, const int *cu, void *Kc, void *Vc,
+                         int *seg_len, int *overflow, hipStream_t s);
+
 
 // Profiling aid (adakv_trace_arm): while armed on this host thread, an event is recorded on the
 // stream in front of every kernel and at the end of every ABI call.

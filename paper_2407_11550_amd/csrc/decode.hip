@@ -1,0 +1,431 @@
+// Decode side of the flattened per-head cache (Section 3.5): the cache update of Eq. (1) and
+// one decoding step of Eq. (2) per query head over segments of different lengths.
+//
+// Layout: segment s = b*h_kv + c starts at row cu[s] + s*headroom of K_cache / V_cache and holds
+// seg_len[s] rows of ROWB = d*sizeof(T) bytes, so a segment is one contiguous byte range.
+//
+// Attention: HBM-bound (every cached K and V row is read once, 2*ROWB bytes for 4*g*d flops),
+// and with g <= 8 query rows per segment far too thin for the matrix cores, so the products
+// run on the vector ALUs.  A row is read by LPR = ROWB/16 neighbouring lanes, 16 bytes each:
+// every load instruction of a wavefront fetches 64/LPR whole rows = 1 KB of consecutive memory.
+// Segment lengths live on the device, so the host launches an upper bound of workgroups
+// (capacity / split + segments); each workgroup finds its (segment, split) from a prefix sum of
+// the lengths, writes partial (max, sum, weighted value sum) per query head, and a second kernel
+// merges the splits of each segment.
+#include <math.h>
+
+#include "common.h"
+
+namespace adakv {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+constexpr float M_INIT = -1.0e30f;    // finite "no row seen yet" maximum: exp2(-inf - M_INIT) = 0
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false);
+  return x + __builtin_bit_cast(float, y);
+}
+
+// Sum over the LPR neighbouring lanes that share a row; every one of them gets the sum.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+  x = dpp_add<0xB1>(x);                       // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                       // quad_perm [2,3,0,1]
+  if (LPR >= 8) x = dpp_add<0x141>(x);        // row_half_mirror: lane i <-> 7-i
+  if (LPR >= 16) x = dpp_add<0x140>(x);       // row_mirror: lane i <-> 15-i
+  if (LPR >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<unsigned short> {     // bf16: 8 elements per 16 bytes
+  static constexpr int EPL = 8;
+  static __device__ __forceinline__ void widen(u32x4 v, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __builtin_bit_cast(float, v[i] << 16);
+      f[2 * i + 1] = __builtin_bit_cast(float, v[i] & 0xffff0000u);
+    }
+  }
+};
+template <> struct Elem<float> {
+  static constexpr int EPL = 4;
+  static __device__ __forceinline__ void widen(u32x4 v, float (&f)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned int word = v[i];          // a copy: bit_cast of the vector element itself
+      f[i] = __builtin_bit_cast(float, word);  // reads element 0 for every i
+    }
+  }
+};
+
+__device__ __forceinline__ int rows_held(const int *cu, const int *seg_len, int s, int headroom) {
+  const int cap = cu[s + 1] - cu[s] + headroom;
+  return min(max(seg_len[s], 0), cap);         // a corrupt length can never leave the segment
+}
+
+// Blocks of `split` rows per segment, summed over the segments in front of segment `s_first` of
+// this thread's run (thread t owns segments t*per .. t*per+per-1).  Returns the exclusive prefix;
+// *total gets the sum over all segments.  One call per kernel; uses sh[0..4].
+__device__ __forceinline__ int scan_blocks(int nseg, int per, int split, int headroom,
+                                           const int *cu, const int *seg_len, int *sh,
+                                           int *total) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int mine = 0;
+  for (int i = 0; i < per; ++i) {
+    const int s = tid * per + i;
+    if (s < nseg) mine += (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
+  }
+  int inc = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(inc, o);
+    if (lane >= o) inc += y;
+  }
+  if (lane == 63) sh[wv] = inc;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = sh[i];
+    if (i < wv) before += v;
+    all += v;
+  }
+  *total = all;
+  return before + inc - mine;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void decode_attn_kernel(
+    int nseg, int h, int per, int split, int headroom, float c_log2, const T *__restrict__ q,
+    const int *__restrict__ cu, const int *__restrict__ seg_len, const char *__restrict__ Kc,
+    const char *__restrict__ Vc, float *__restrict__ part_acc, float *__restrict__ part_ml) {
+  constexpr int EPL = Elem<T>::EPL;
+  constexpr int ROWB = D * (int)sizeof(T);
+  constexpr int LPR = ROWB / 16;               // lanes per row
+  constexpr int RPW = 64 / LPR;                // rows per wavefront load
+  constexpr int NW = 4;
+  // With many query rows per KV head the widened queries alone would take G*EPL registers: they
+  // then stay packed as loaded and are widened at every use, and fewer row loads are in flight.
+  constexpr bool PACKQ = G * EPL > 32;
+  constexpr int U = PACKQ ? 2 : 4;             // row loads in flight per lane, for K and for V
+
+  __shared__ int sh_scan[8];
+  __shared__ float sh_acc[NW][G][D];
+  __shared__ float sh_m[NW][G], sh_l[NW][G];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane % LPR, slot = lane / LPR;
+
+  // ---- which (segment, split) is this workgroup? -------------------------------------------
+  int total;
+  const int excl = scan_blocks(nseg, per, split, headroom, cu, seg_len, sh_scan, &total);
+  if ((int)blockIdx.x >= total) return;        // uniform: the launch is an upper bound
+  {
+    int first = excl;
+    for (int i = 0; i < per; ++i) {
+      const int s = tid * per + i;
+      if (s >= nseg) break;
+      const int nb = (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
+      if ((int)blockIdx.x >= first && (int)blockIdx.x < first + nb) {
+        sh_scan[4] = s;
+        sh_scan[5] = (int)blockIdx.x - first;
+      }
+      first += nb;
+    }
+  }
+  __syncthreads();
+  const int s = sh_scan[4], j = sh_scan[5];
+  const int b = s / h, c = s % h;
+  const int len = rows_held(cu, seg_len, s, headroom);
+  const int r0 = j * split, r1 = min(len, r0 + split);
+  const long long seg_byte = ((long long)cu[s] + (long long)s * headroom) * ROWB + col * 16;
+  const char *Kb = Kc + seg_byte;
+  const char *Vb = Vc + seg_byte;
+
+  // ---- the g query rows of this KV head, pre-scaled so that exp() becomes exp2() --------------
+  float qf[PACKQ ? 1 : G][EPL];
+  u32x4 qp16[PACKQ ? G : 1];
+#pragma unroll
+  for (int gi = 0; gi < G; ++gi) {
+    const T *qp = q + ((long long)(b * h + c) * G + gi) * D + col * EPL;
+    const u32x4 raw = *reinterpret_cast<const u32x4 *>(qp);
+    if constexpr (PACKQ) {
+      qp16[gi] = raw;
+    } else {
+      Elem<T>::widen(raw, qf[gi]);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qf[gi][e] *= c_log2;
+    }
+  }
+
+  float m[G], l[G], acc[G][EPL];
+#pragma unroll
+  for (int gi = 0; gi < G; ++gi) {
+    m[gi] = M_INIT; l[gi] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[gi][e] = 0.0f;
+  }
+
+  const int rows = r1 - r0;
+  const int iters = (rows + U * NW * RPW - 1) / (U * NW * RPW);
+  for (int it = 0; it < iters; ++it) {
+    u32x4 kk[U], vv[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = r0 + ((it * U + u) * NW + wv) * RPW + slot;
+      ok[u] = r < r1;
+      const long long o = (long long)min(r, r1 - 1) * ROWB;    // r1 >= 1: the block exists
+      kk[u] = *reinterpret_cast<const u32x4 *>(Kb + o);
+      vv[u] = *reinterpret_cast<const u32x4 *>(Vb + o);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL], sc[G];
+      Elem<T>::widen(kk[u], kf);
+      bool grow = false;
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi) {
+        float a = 0.0f;
+        if constexpr (PACKQ) {
+          float qw[EPL];
+          u32x4 packed = qp16[gi];
+          asm volatile("" : "+v"(packed));     // keeps the widening inside the loop
+          Elem<T>::widen(packed, qw);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) a = fmaf(qw[e], kf[e], a);
+          a *= c_log2;
+        } else {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) a = fmaf(qf[gi][e], kf[e], a);
+        }
+        a = row_sum<LPR>(a);
+        sc[gi] = ok[u] ? a : -INFINITY;
+        grow |= sc[gi] > m[gi];
+      }
+      if (__any(grow)) {                       // a new running maximum somewhere in the wavefront
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+          const float mn = fmaxf(m[gi], sc[gi]);
+          const float corr = fast_exp2(m[gi] - mn);
+          l[gi] *= corr;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[gi][e] *= corr;
+          m[gi] = mn;
+        }
+      }
+      float vf[EPL];
+      Elem<T>::widen(vv[u], vf);
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi) {
+        const float p = fast_exp2(sc[gi] - m[gi]);
+        l[gi] += p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[gi][e] = fmaf(p, vf[e], acc[gi][e]);
+      }
+    }
+  }
+
+  // ---- merge the RPW row slots of the wavefront, then the NW wavefronts ----------------------
+#pragma unroll
+  for (int gi = 0; gi < G; ++gi) {
+    float M = m[gi];
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
+    const float f = fast_exp2(m[gi] - M);
+    float ll = l[gi] * f;
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) ll += __shfl_xor(ll, o);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float a = acc[gi][e] * f;
+#pragma unroll
+      for (int o = LPR; o < 64; o <<= 1) a += __shfl_xor(a, o);
+      acc[gi][e] = a;
+    }
+    if (slot == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sh_acc[wv][gi][col * EPL + e] = acc[gi][e];
+      if (col == 0) { sh_m[wv][gi] = M; sh_l[wv][gi] = ll; }
+    }
+  }
+  __syncthreads();
+  for (int t = tid; t < G * D; t += 256) {
+    const int gi = t / D, e = t % D;
+    float M = sh_m[0][gi];
+#pragma unroll
+    for (int w2 = 1; w2 < NW; ++w2) M = fmaxf(M, sh_m[w2][gi]);
+    float a = 0.0f, ll = 0.0f;
+#pragma unroll
+    for (int w2 = 0; w2 < NW; ++w2) {
+      const float f = fast_exp2(sh_m[w2][gi] - M);
+      a = fmaf(sh_acc[w2][gi][e], f, a);
+      ll = fmaf(sh_l[w2][gi], f, ll);
+    }
+    part_acc[((long long)blockIdx.x * G + gi) * D + e] = a;
+    if (e == 0) {
+      part_ml[((long long)blockIdx.x * G + gi) * 2] = M;
+      part_ml[((long long)blockIdx.x * G + gi) * 2 + 1] = ll;
+    }
+  }
+}
+
+// One workgroup per segment merges that segment's splits and normalises.
+template <int D, int G>
+__global__ __launch_bounds__(256) void decode_combine_kernel(
+    int nseg, int h, int per, int split, int headroom, const int *__restrict__ cu,
+    const int *__restrict__ seg_len, const float *__restrict__ part_acc,
+    const float *__restrict__ part_ml, float *__restrict__ out, float *__restrict__ lse) {
+  __shared__ int sh_scan[8];
+  const int tid = threadIdx.x;
+  const int s = blockIdx.x;
+  int total;
+  const int excl = scan_blocks(nseg, per, split, headroom, cu, seg_len, sh_scan, &total);
+  if (s >= tid * per && s < tid * per + per) {
+    int first = excl;
+    for (int i = 0; tid * per + i < s; ++i)
+      first += (rows_held(cu, seg_len, tid * per + i, headroom) + split - 1) / split;
+    sh_scan[4] = first;
+  }
+  __syncthreads();
+  const int p0 = sh_scan[4];
+  const int cnt = (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
+  const int b = s / h, c = s % h;
+  for (int t = tid; t < G * D; t += 256) {
+    const int gi = t / D, e = t % D;
+    float M = M_INIT;
+    for (int p = 0; p < cnt; ++p) M = fmaxf(M, part_ml[((long long)(p0 + p) * G + gi) * 2]);
+    float a = 0.0f, ll = 0.0f;
+    for (int p = 0; p < cnt; ++p) {
+      const long long pg = (long long)(p0 + p) * G + gi;
+      const float f = fast_exp2(part_ml[pg * 2] - M);
+      a = fmaf(part_acc[pg * D + e], f, a);
+      ll = fmaf(part_ml[pg * 2 + 1], f, ll);
+    }
+    const long long row = (long long)(b * h + c) * G + gi;
+    out[row * D + e] = ll > 0.0f ? a / ll : 0.0f;
+    if (lse && e == 0) lse[row] = ll > 0.0f ? (M + log2f(ll)) * LN2 : -INFINITY;
+  }
+}
+
+// Eq. (1) for every segment: LPR lanes move the new K row and the new V row of one segment.
+template <int LPR>
+__global__ __launch_bounds__(256) void append_kernel(
+    int nseg, int headroom, const char *__restrict__ k_new, const char *__restrict__ v_new,
+    const int *__restrict__ cu, char *__restrict__ Kc, char *__restrict__ Vc,
+    int *__restrict__ seg_len, int *__restrict__ overflow) {
+  const int s = (blockIdx.x * 256 + threadIdx.x) / LPR;
+  const int col = threadIdx.x % LPR;
+  if (s >= nseg) return;
+  const int cap = cu[s + 1] - cu[s] + headroom;
+  const int len = seg_len[s];                  // read by all LPR lanes before lane 0 stores
+  if (len < 0 || len >= cap) {
+    if (col == 0 && overflow) *overflow = 1;
+    return;
+  }
+  const uint4 kv = *reinterpret_cast<const uint4 *>(k_new + ((long long)s * LPR + col) * 16);
+  const uint4 vv = *reinterpret_cast<const uint4 *>(v_new + ((long long)s * LPR + col) * 16);
+  const long long o = (((long long)cu[s] + (long long)s * headroom + len) * LPR + col) * 16;
+  *reinterpret_cast<uint4 *>(Kc + o) = kv;
+  *reinterpret_cast<uint4 *>(Vc + o) = vv;
+  if (col == 0) seg_len[s] = len + 1;
+}
+
+template <typename T, int D, int G>
+void run_decode(const SeqTab &st, const Dims &dm, int headroom, const DecodePlan &pl,
+                const void *q, const int *cu, const void *Kc, const void *Vc, const int *seg_len,
+                float *out, float *lse, char *ws, hipStream_t s) {
+  const int nseg = st.batch * dm.h_kv;
+  const int per = (nseg + 255) / 256;
+  float *part_acc = (float *)(ws + pl.part_acc);
+  float *part_ml = (float *)(ws + pl.part_ml);
+  ADAKV_LAUNCH("decode_attn", (decode_attn_kernel<T, D, G>), dim3(pl.nblk), dim3(256), s, nseg,
+               dm.h_kv, per, pl.split, headroom, dm.scale * LOG2E, (const T *)q, cu, seg_len,
+               (const char *)Kc, (const char *)Vc, part_acc, part_ml);
+  ADAKV_LAUNCH("decode_combine", (decode_combine_kernel<D, G>), dim3(nseg), dim3(256), s, nseg,
+               dm.h_kv, per, pl.split, headroom, cu, seg_len, (const float *)part_acc,
+               (const float *)part_ml, out, lse);
+}
+
+template <typename T, int D>
+bool run_decode_g(const SeqTab &st, const Dims &dm, int headroom, const DecodePlan &pl,
+                  const void *q, const int *cu, const void *Kc, const void *Vc,
+                  const int *seg_len, float *out, float *lse, char *ws, hipStream_t s) {
+  switch (dm.g) {
+    case 1: run_decode<T, D, 1>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
+    case 2: run_decode<T, D, 2>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
+    case 4: run_decode<T, D, 4>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
+    case 8: run_decode<T, D, 8>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
+    default: return false;
+  }
+}
+
+}  // namespace
+
+bool decode_supported(const Dims &dm) {
+  return (dm.g == 1 || dm.g == 2 || dm.g == 4 || dm.g == 8) && (dm.d == 64 || dm.d == 128);
+}
+
+DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom) {
+  DecodePlan pl;
+  const long long nseg = (long long)st.batch * dm.h_kv;
+  const long long cap = (long long)st.out_off[st.batch] + nseg * headroom;
+  // rows per workgroup: as long as possible while about a thousand workgroups remain
+  int split = 1024;
+  while (split > 64 && cap / split < 1024) split >>= 1;
+  pl.split = split;
+  pl.nblk = (int)(cap / split + nseg);          // >= sum over segments of ceil(len / split)
+  pl.part_acc = 0;
+  pl.part_ml = align_up((size_t)pl.nblk * dm.g * dm.d * sizeof(float), 256);
+  pl.total = pl.part_ml + align_up((size_t)pl.nblk * dm.g * 2 * sizeof(float), 256);
+  return pl;
+}
+
+hipError_t launch_decode_attn(const SeqTab &st, const Dims &dm, int dtype, int headroom,
+                              const void *q, const int *cu, const void *Kc, const void *Vc,
+                              const int *seg_len, float *out, float *lse, char *ws,
+                              hipStream_t s) {
+  const DecodePlan pl = plan_decode(st, dm, headroom);
+  bool ok;
+  if (dtype == ADAKV_BF16) {
+    ok = dm.d == 64 ? run_decode_g<unsigned short, 64>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s)
+                    : run_decode_g<unsigned short, 128>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s);
+  } else {
+    ok = dm.d == 64 ? run_decode_g<float, 64>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s)
+                    : run_decode_g<float, 128>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s);
+  }
+  if (!ok) return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_append(const SeqTab &st, const Dims &dm, int dtype, int headroom,
+                         const void *k_new, const void *v_new, const int *cu, void *Kc, void *Vc,
+                         int *seg_len, int *overflow, hipStream_t s) {
+  const int lpr = dm.d * (dtype == ADAKV_BF16 ? 2 : 4) / 16;
+  const int nseg = st.batch * dm.h_kv;
+  dim3 grid((nseg * lpr + 255) / 256), block(256);
+#define ADAKV_LAUNCH_APPEND(LPR)                                                               \
+  ADAKV_LAUNCH("append", append_kernel<LPR>, grid, block, s, nseg, headroom,                   \
+               (const char *)k_new, (const char *)v_new, cu, (char *)Kc, (char *)Vc, seg_len,  \
+               overflow)
+  switch (lpr) {
+    case 8: ADAKV_LAUNCH_APPEND(8); break;
+    case 16: ADAKV_LAUNCH_APPEND(16); break;
+    case 32: ADAKV_LAUNCH_APPEND(32); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef ADAKV_LAUNCH_APPEND
+  return hipGetLastError();
+}
+
+}  // namespace adakv

@@ -159,3 +159,62 @@ def concentration(scores_head: np.ndarray, top_fraction: float = 0.05) -> float:
     v = np.sort(np.asarray(scores_head, dtype=np.float64))[::-1]
     k = max(1, int(round(top_fraction * v.size)))
     return float(v[:k].sum() / v.sum())
+
+
+# ---- decode side: compressed caches of uneven per-head length, and per-step inputs -------------
+def skewed_budgets(wl: Workload, seed: int = 0, skew: float = 1.5):
+    """Per-segment prefix budgets [batch*h_kv] with sum over the heads of sequence b equal to
+    B_b - w*h_kv, spread unevenly (weights exp(skew * N(0,1)), capped at n_b): the kind of
+    length mix adaptive allocation produces (a few long heads, some holding little more than
+    the window).  A description of inputs only; no part of the allocation rule."""
+    rng = np.random.Generator(np.random.PCG64(10_000 + seed))
+    out = []
+    for nb, Bb in zip(wl.n, wl.B):
+        Bp = Bb - wl.w * wl.h_kv
+        wgt = np.exp(skew * rng.standard_normal(wl.h_kv))
+        raw = np.minimum(np.floor(Bp * wgt / wgt.sum()).astype(np.int64), nb)
+        left = Bp - int(raw.sum())
+        c = 0
+        while left > 0:                       # hand the remainder out wherever there is room
+            room = nb - int(raw[c % wl.h_kv])
+            take = min(room, left)
+            raw[c % wl.h_kv] += take
+            left -= take
+            c += 1
+        out.extend(int(v) for v in raw)
+    return out
+
+
+def ragged_cache(wl: Workload, budgets, headroom: int, seed: int = 0, device="cpu"):
+    """A compressed cache in the flattened layout without running the compression: segment
+    s = b*h_kv + c holds budgets[s] + w rows of N(0,1) keys and values (in wl.dtype) at row
+    cu[s] + s*headroom; spare rows are zero.  Returns (K_cache, V_cache, cu_seqlens, seg_len),
+    the last two int32."""
+    dev = torch.device(device)
+    tg = torch.Generator(device=dev)
+    tg.manual_seed(20_000 + seed)
+    lens = [int(b) + wl.w for b in budgets]
+    cu = [0]
+    for v in lens:
+        cu.append(cu[-1] + v)
+    rows = cu[-1] + len(lens) * headroom
+    Kc = torch.zeros((rows, wl.d), dtype=wl.dtype, device=dev)
+    Vc = torch.zeros((rows, wl.d), dtype=wl.dtype, device=dev)
+    for s, L in enumerate(lens):
+        a = cu[s] + s * headroom
+        Kc[a:a + L] = torch.randn((L, wl.d), generator=tg, dtype=torch.float32, device=dev).to(wl.dtype)
+        Vc[a:a + L] = torch.randn((L, wl.d), generator=tg, dtype=torch.float32, device=dev).to(wl.dtype)
+    return (Kc, Vc, torch.tensor(cu, dtype=torch.int32, device=dev),
+            torch.tensor(lens, dtype=torch.int32, device=dev))
+
+
+def decode_inputs(wl: Workload, steps: int, seed: int = 0, device="cpu", temp: float = 2.0):
+    """Per-step decode inputs in wl.dtype: q_new [steps, batch, h_q, d] (N(0,1) times `temp`,
+    so that the softmax is neither flat nor one-hot), k_new, v_new [steps, batch, h_kv, d]."""
+    dev = torch.device(device)
+    tg = torch.Generator(device=dev)
+    tg.manual_seed(30_000 + seed)
+    q = temp * torch.randn((steps, wl.batch, wl.h_q, wl.d), generator=tg, dtype=torch.float32, device=dev)
+    k = torch.randn((steps, wl.batch, wl.h_kv, wl.d), generator=tg, dtype=torch.float32, device=dev)
+    v = torch.randn((steps, wl.batch, wl.h_kv, wl.d), generator=tg, dtype=torch.float32, device=dev)
+    return q.to(wl.dtype), k.to(wl.dtype), v.to(wl.dtype)

@@ -1,0 +1,192 @@
+"""GPU parity of the decode side (adakv_cache_build, adakv_append, adakv_decode_attn) against
+the CPU oracle on the same seeded inputs.
+
+Bars: cache_build and append are byte movement and integer bookkeeping: bit-exact.
+decode_attn is fp32 arithmetic on bf16/fp32 inputs against fp64: a logit carries an absolute
+error of a few 1e-6 (d products, fp32 accumulation, magnitudes up to ~20), the exponential is
+good to a few ulp, and L weighted value rows are summed in fp32, so an output element is off
+by some 1e-6 * max|V| at most for the lengths here; the bar is 5e-5 * max|V| absolute plus 2e-3
+relative (the relative part is the tolerance the scoring path is held to), and 2e-5 absolute
+for lse."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_11550_amd as adakv
+from oracle import adakv_oracle as O
+from oracle import decode_oracle as D
+from paper_2407_11550_amd import synth
+
+from parity_util import to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+OUT_ATOL_PER_VMAX = 5e-5
+OUT_RTOL = 2e-3
+LSE_ATOL = 2e-5
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _assert_decode_close(out, lse, ref_out, ref_lse, vmax, what):
+    out = to_f64(out); ref_out = np.asarray(ref_out)
+    assert np.all(np.isfinite(out)), what
+    err = np.abs(out - ref_out)
+    bad = err > OUT_ATOL_PER_VMAX * vmax + OUT_RTOL * np.abs(ref_out)
+    assert not bad.any(), f"{what}: {int(bad.sum())} of {out.size} outputs off, worst abs err {err.max():.3e}"
+    if lse is not None:
+        lse = to_f64(lse)
+        fin = np.isfinite(ref_lse)
+        assert np.array_equal(np.isneginf(lse), ~fin), what
+        assert np.abs(lse[fin] - ref_lse[fin]).max(initial=0.0) <= LSE_ATOL + 1e-6 * np.abs(ref_lse[fin]).max(initial=0.0), \
+            f"{what}: lse off by {np.abs(lse[fin] - ref_lse[fin]).max():.3e}"
+
+
+def _decode_case(h_q, h, d, w, n, per_head, dtype, headroom, seed, skew=1.5):
+    n = list(n)
+    B = [h * (w + per_head)] * len(n)
+    wl = synth.small_workload(h_q, h, d, w, 7, n, B, dtype=dtype, seed=seed)
+    budgets = synth.skewed_budgets(wl, seed=seed, skew=skew)
+    Kc, Vc, cu, seg_len = synth.ragged_cache(wl, budgets, headroom, seed=seed, device=DEV)
+    return wl, adakv.Layer.from_workload(wl), Kc, Vc, cu, seg_len
+
+
+DECODE_SHAPES = [
+    # h_q h_kv d   w   n per sequence       rows/head  dtype         headroom
+    (8, 2, 128, 4, [400], 60, torch.bfloat16, 0),              # g 4, a few blocks, tight layout
+    (32, 8, 128, 32, [9000, 3000], 700, torch.bfloat16, 16),   # Llama-3.1-8B heads, two sequences
+    (4, 4, 64, 8, [1024], 120, torch.float32, 3),              # fp32, d 64, no GQA
+    (16, 2, 128, 2, [5000], 2400, torch.bfloat16, 5),          # g 8 (70B-like group), long segments
+    (4, 2, 64, 1, [300, 200, 100], 40, torch.bfloat16, 1),     # g 2, d 64, three sequences
+    (8, 8, 128, 4, [2000], 500, torch.float32, 7),             # fp32 d 128: 32 lanes per row
+    (2, 1, 128, 1, [50], 0, torch.bfloat16, 2),                # segments of one row
+    (4, 4, 128, 8, [1024], 120, torch.bfloat16, 3),            # bf16 without GQA
+    (8, 2, 64, 8, [1024], 120, torch.float32, 3),              # fp32 with g 4
+]
+
+
+@pytest.mark.parametrize("shape", DECODE_SHAPES, ids=lambda s: "hq%d_h%d_d%d_w%d_n%d_r%d_%s_hr%d" % (
+    s[0], s[1], s[2], s[3], s[4][0], s[5], str(s[6])[6:], s[7]))
+def test_decode_attn_matches_oracle(shape):
+    h_q, h, d, w, n, per_head, dt, hr = shape
+    _say(f"decode_attn {shape}")
+    wl, layer, Kc, Vc, cu, seg_len = _decode_case(h_q, h, d, w, n, per_head, dt, hr, seed=21)
+    q, _, _ = synth.decode_inputs(wl, 1, seed=21, device=DEV)
+    out, lse = adakv.decode_attn(layer, q[0], cu, hr, Kc, Vc, seg_len, want_lse=True)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = D.decode_attention(to_f64(q[0]), to_f64(Kc), to_f64(Vc), cu.cpu().numpy(), hr,
+                                          seg_len.cpu().numpy(), wl.g)
+    _assert_decode_close(out, lse, ref_out, ref_lse, float(Vc.float().abs().max()), str(shape))
+
+
+def test_decode_attn_many_rows_several_splits_per_segment():
+    """Enough rows that the rows-per-workgroup choice leaves its minimum and long segments are cut
+    into many splits."""
+    _say("decode_attn large")
+    wl, layer, Kc, Vc, cu, seg_len = _decode_case(32, 8, 128, 32, [60000, 40000], 12000, torch.bfloat16, 64,
+                                                  seed=5, skew=2.0)
+    q, _, _ = synth.decode_inputs(wl, 1, seed=5, device=DEV)
+    out, lse = adakv.decode_attn(layer, q[0], cu, 64, Kc, Vc, seg_len, want_lse=True)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = D.decode_attention(to_f64(q[0]), to_f64(Kc), to_f64(Vc), cu.cpu().numpy(), 64,
+                                          seg_len.cpu().numpy(), wl.g)
+    _assert_decode_close(out, lse, ref_out, ref_lse, float(Vc.float().abs().max()), "large")
+    assert int(seg_len.max()) > 8 * int(seg_len.min())          # the length mix really is uneven
+
+
+def test_decode_attn_empty_segment_and_custom_scale():
+    _say("decode_attn empty segment")
+    wl, _, Kc, Vc, cu, seg_len = _decode_case(8, 2, 128, 4, [400], 60, torch.bfloat16, 2, seed=3)
+    layer = adakv.Layer.from_workload(wl, scale=0.05)
+    seg_len[1] = 0
+    q, _, _ = synth.decode_inputs(wl, 1, seed=3, device=DEV)
+    out, lse = adakv.decode_attn(layer, q[0], cu, 2, Kc, Vc, seg_len, want_lse=True)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = D.decode_attention(to_f64(q[0]), to_f64(Kc), to_f64(Vc), cu.cpu().numpy(), 2,
+                                          seg_len.cpu().numpy(), wl.g, scale=0.05)
+    _assert_decode_close(out, lse, ref_out, ref_lse, float(Vc.float().abs().max()), "empty")
+    assert not out[0, 4:].any() and torch.isneginf(lse[0, 4:]).all()
+
+
+def test_cache_build_is_the_gather_with_head_room_bit_exact():
+    _say("cache_build")
+    wl = synth.small_workload(8, 2, 128, 8, 7, [700, 300], [2 * 90, 2 * 40], seed=9)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl)
+    res = adakv.compress(layer, q, K, V)
+    hr = 6
+    rows = adakv.cache_rows(layer, hr)
+    Kc = torch.full((rows + 3, wl.d), -7.0, dtype=wl.dtype, device=DEV)    # canaries in spare rows and past the end
+    Vc = torch.full((rows + 3, wl.d), -9.0, dtype=wl.dtype, device=DEV)
+    _, _, seg_len = adakv.cache_build(layer, K, V, res["indices"], res["cu_seqlens"], hr, Kc, Vc)
+    torch.cuda.synchronize()
+    cu = res["cu_seqlens"].cpu().numpy()
+    rK, rV, rlen = D.build_cache(res["K_out"].float().cpu().numpy(), res["V_out"].float().cpu().numpy(), cu, hr)
+    assert np.array_equal(seg_len.cpu().numpy(), rlen)
+    gK, gV = Kc.float().cpu().numpy(), Vc.float().cpu().numpy()
+    start = D.segment_starts(cu, hr)
+    used = np.zeros(rows + 3, bool)
+    for s in range(len(rlen)):
+        used[start[s]:start[s] + rlen[s]] = True
+    assert np.array_equal(gK[:rows][used[:rows]], rK[used[:rows]]) and np.array_equal(gV[:rows][used[:rows]], rV[used[:rows]])
+    assert (gK[~used] == -7.0).all() and (gV[~used] == -9.0).all()          # nothing else was written
+
+
+def test_append_then_attend_matches_oracle_step_by_step_and_reports_overflow():
+    _say("append + decode chain")
+    wl = synth.small_workload(8, 2, 128, 8, 7, [700, 300], [2 * 90, 2 * 40], seed=13)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl)
+    res = adakv.compress(layer, q, K, V)
+    hr, steps = 3, 5
+    rows = adakv.cache_rows(layer, hr)
+    Kc = torch.zeros((rows, wl.d), dtype=wl.dtype, device=DEV)
+    Vc = torch.zeros((rows, wl.d), dtype=wl.dtype, device=DEV)
+    _, _, seg_len = adakv.cache_build(layer, K, V, res["indices"], res["cu_seqlens"], hr, Kc, Vc)
+    overflow = torch.zeros(1, dtype=torch.int32, device=DEV)
+    torch.cuda.synchronize()
+    cu = res["cu_seqlens"].cpu().numpy()
+    oK, oV, olen = to_f64(Kc), to_f64(Vc), seg_len.cpu().numpy().astype(np.int64)
+    qn, kn, vn = synth.decode_inputs(wl, steps, seed=13, device=DEV)
+    ws = torch.empty(adakv.decode_workspace_bytes(layer, hr), dtype=torch.uint8, device=DEV)
+    vmax = float(Vc.float().abs().max())
+    for t in range(steps):
+        adakv.append(layer, kn[t], vn[t], res["cu_seqlens"], hr, Kc, Vc, seg_len, overflow=overflow)
+        out, lse = adakv.decode_attn(layer, qn[t], res["cu_seqlens"], hr, Kc, Vc, seg_len, ws=ws, want_lse=True)
+        torch.cuda.synchronize()
+        full = D.append(oK, oV, cu, hr, olen, to_f64(kn[t]).reshape(-1, wl.d), to_f64(vn[t]).reshape(-1, wl.d))
+        assert np.array_equal(seg_len.cpu().numpy(), olen), t
+        assert bool(overflow.item()) == (full or t >= hr), t
+        start = D.segment_starts(cu, hr)
+        gK, gV = to_f64(Kc), to_f64(Vc)
+        for s in range(len(olen)):
+            assert np.array_equal(gK[start[s]:start[s] + olen[s]], oK[start[s]:start[s] + olen[s]])
+            assert np.array_equal(gV[start[s]:start[s] + olen[s]], oV[start[s]:start[s] + olen[s]])
+        ref_out, ref_lse = D.decode_attention(to_f64(qn[t]), oK, oV, cu, hr, olen, wl.g)
+        _assert_decode_close(out, lse, ref_out, ref_lse, vmax, f"step {t}")
+    assert (olen == (cu[1:] - cu[:-1]) + hr).all()               # every segment ended up full
+
+
+def test_decode_rejects_bad_arguments():
+    _say("decode argument checks")
+    wl = synth.small_workload(6, 2, 128, 4, 7, [100], [2 * 20], seed=1)      # g = 3: not supported
+    layer = adakv.Layer.from_workload(wl)
+    assert adakv.decode_workspace_bytes(layer, 4) == 0
+    budgets = synth.skewed_budgets(wl)
+    Kc, Vc, cu, seg_len = synth.ragged_cache(wl, budgets, 4, device=DEV)
+    q, _, _ = synth.decode_inputs(wl, 1, device=DEV)
+    with pytest.raises(adakv.AdaKVError) as e:
+        adakv.decode_attn(layer, q[0], cu, 4, Kc, Vc, seg_len, ws=torch.empty(1 << 20, dtype=torch.uint8, device=DEV))
+    assert e.value.status == -2
+    wl2 = synth.small_workload(8, 2, 128, 4, 7, [100], [2 * 20], seed=1)
+    layer2 = adakv.Layer.from_workload(wl2)
+    Kc, Vc, cu, seg_len = synth.ragged_cache(wl2, synth.skewed_budgets(wl2), 4, device=DEV)
+    q, _, _ = synth.decode_inputs(wl2, 1, device=DEV)
+    with pytest.raises(adakv.AdaKVError) as e:
+        adakv.decode_attn(layer2, q[0], cu, 4, Kc, Vc, seg_len, ws=torch.empty(16, dtype=torch.uint8, device=DEV))
+    assert e.value.status == -3
+    with pytest.raises(adakv.AdaKVError) as e:
+        adakv.decode_attn(layer2, q[0], cu, -1, Kc, Vc, seg_len, ws=torch.empty(1 << 20, dtype=torch.uint8, device=DEV))
+    assert e.value.status == -1

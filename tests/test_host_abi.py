@@ -120,3 +120,26 @@ def test_generator_is_deterministic_and_shaped():
         w = synth.workload(nm)
         for nb, Bb in zip(w.n, w.B):
             assert w.w * w.h_kv <= Bb <= w.w * w.h_kv + w.h_kv * nb
+
+
+def test_decode_side_argument_checks(lib):
+    L = _layer()
+    one = ctypes.c_void_p(16)
+    by = ctypes.byref(L.c)
+    assert adakv.decode_workspace_bytes(L, 0) > 0
+    assert adakv.decode_workspace_bytes(L, 64) >= adakv.decode_workspace_bytes(L, 0)
+    assert adakv.decode_workspace_bytes(L, -1) == 0
+    assert adakv.decode_workspace_bytes(_layer(h_q=24), 4) == 0          # g = 3 has no kernel
+    assert adakv.decode_workspace_bytes(_layer(w=0), 4) == 0
+    # invalid head-room, NULL pointers, unsupported group size, workspace too small
+    assert lib.adakv_cache_build(by, one, one, one, one, -1, one, one, one, None) == -1
+    assert lib.adakv_cache_build(by, one, one, one, one, 4, None, one, one, None) == -1
+    assert lib.adakv_cache_build(by, one, one, one, one, 1 << 30, one, one, one, None) == -2   # rows >= 2^31
+    assert lib.adakv_append(by, one, None, one, 4, one, one, one, None, None) == -1
+    assert lib.adakv_append(by, one, one, one, -5, one, one, one, None, None) == -1
+    assert lib.adakv_decode_attn(by, one, one, 4, one, one, one, None, None, one, 1 << 30, None) == -1
+    assert lib.adakv_decode_attn(by, one, one, 4, one, one, one, one, None, one, 8, None) == -3
+    assert lib.adakv_decode_attn(by, one, one, 4, one, one, one, one, None, None, 1 << 30, None) == -3
+    L3 = _layer(h_q=24)
+    assert lib.adakv_decode_attn(ctypes.byref(L3.c), one, one, 4, one, one, one, one, None, one, 1 << 30, None) == -2
+    assert adakv.cache_rows(L, 5) == L.num_rows_out + L.num_segments * 5
