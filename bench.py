@@ -7,6 +7,10 @@ layer.  Inputs are resident in HBM before the timed region; the step rotates ove
 distinct input sets (more than a gigabyte in total, against 256 MB of memory-side cache) so
 that the K stream really comes from HBM.
 
+`--path decode` measures the decode side of the flattened cache instead (one step = one
+adakv_append + one adakv_decode_attn over the layer's compressed cache, built by the same
+compression with `--budget-frac` of every prefix kept); the default is the compression step.
+
 Prints ONE JSON line.  `value` is prefix tokens compressed per second (the layer's n divided
 by the time of a step).  `roofline` describes the dominant kernel, timed live with events
 recorded in front of and behind it on the launch stream (adakv_trace_arm) in a second pass
@@ -43,6 +47,108 @@ def algorithmic_bytes(wl, kept_rows):
             "compact": gather + kept_rows * 4, "k_stream": k_stream}
 
 
+def bench_decode(args):
+    """One step = adakv_append + adakv_decode_attn for every sequence and head of one layer, on
+    the cache the compression step produced."""
+    import numpy as np
+    import torch
+
+    import paper_2407_11550_amd as adakv
+    from paper_2407_11550_amd import synth
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.workload(args.workload, alpha=args.alpha)
+    if args.budget_frac is not None:
+        wl.B = [wl.h_kv * (wl.w + max(1, int(round(args.budget_frac * nb)))) for nb in wl.n]
+    layer = adakv.Layer.from_workload(wl)
+    trace_steps = min(args.steps, 50)
+    hr = args.warmup + args.steps + trace_steps
+    sets = []
+    for i in range(args.sets):
+        q, K, V = synth.generate(wl, layer=i, device=dev)
+        res = adakv.compress(layer, q, K, V)
+        Kc, Vc, seg_len = adakv.cache_build(layer, K, V, res["indices"], res["cu_seqlens"], hr)
+        sets.append((Kc, Vc, res["cu_seqlens"], seg_len))
+        del q, K, V, res
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    nsteps = 16
+    qn, kn, vn = synth.decode_inputs(wl, nsteps, device=dev)
+    ws = torch.empty(adakv.decode_workspace_bytes(layer, hr), dtype=torch.uint8, device=dev)
+    out = torch.empty((wl.batch, wl.h_q, wl.d), dtype=torch.float32, device=dev)
+    overflow = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def step(i):
+        Kc, Vc, cu, seg_len = sets[i % len(sets)]
+        t = i % nsteps
+        adakv.append(layer, kn[t], vn[t], cu, hr, Kc, Vc, seg_len, overflow=overflow)
+        adakv.decode_attn(layer, qn[t], cu, hr, Kc, Vc, seg_len, out=out, ws=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = 1000.0 * (t1 - t0) / args.steps
+    per_kernel, order, gaps = {}, [], []
+    for i in range(trace_steps):
+        with adakv.KernelTrace(16) as tr:
+            step(i)
+        torch.cuda.synchronize()
+        for name, us in tr.durations_us():
+            if name not in per_kernel:
+                per_kernel[name] = []
+                order.append(name)
+            per_kernel[name].append(us)
+        gaps.extend(tr.marker_gaps_us())
+    assert int(overflow.item()) == 0, "head-room too small for the number of steps"
+    kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
+    marker_us = float(np.median(gaps)) if gaps else 0.0
+    esz = 2 if str(wl.dtype).endswith("bfloat16") else 4
+    rows = float(np.mean([int(s[3].sum().item()) for s in sets]))      # rows held at the end
+    dom_bytes = rows * wl.d * esz * 2                                   # every K and V row once
+    dom_us = max(kernels["decode_attn"] - marker_us, 1e-3)
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode_attn", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "algorithmic_bytes": int(dom_bytes), "avg_us": round(dom_us, 2),
+                "avg_us_between_markers": round(kernels["decode_attn"], 2), "marker_us": round(marker_us, 2)}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+
+        from oracle import decode_oracle as D
+        Kc, Vc, cu, seg_len = sets[0]
+        Kd, Vd = Kc.double().cpu().numpy(), Vc.double().cpu().numpy()
+        cuh, lens = cu.cpu().numpy(), seg_len.cpu().numpy()
+        spent, done = 0.0, 0
+        while spent < 10.0 and done < 64:
+            qd = qn[done % nsteps].double().cpu().numpy()
+            c0 = time.perf_counter()
+            D.decode_attention(qd, Kd, Vd, cuh, hr, lens, wl.g)
+            spent += time.perf_counter() - c0
+            done += 1
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        cpu = {"value": round(done * float(lens.sum()) / spent, 1), "unit": "cached rows/s", "cores": threads,
+               "kind": "oracle", "seconds": round(spent, 3),
+               "sample": f"{done} decode attention step(s) over the whole cache of {wl.name} "
+                         f"({int(lens.sum())} rows), fp64 numpy, the append not included"}
+    print(json.dumps({
+        "metric": "cached K/V rows attended/sec per layer (append + variable-length decode attention)",
+        "value": round(rows / (ms_per_step * 1e-3), 1), "unit": "cached rows/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
+        "config": {"workload": wl.name + " (decode side)", "h_q": wl.h_q, "h_kv": wl.h_kv, "d": wl.d,
+                   "n": wl.n, "w": wl.w, "B": wl.B, "alpha": wl.alpha, "batch": wl.batch,
+                   "cached_rows": int(rows), "headroom": hr, "input_sets_rotated": len(sets)},
+        "kernels_us": {k: round(kernels[k], 2) for k in order}, "roofline": roofline, "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +159,11 @@ def main():
     ap.add_argument("--alpha", type=float, default=None)
     ap.add_argument("--sets", type=int, default=5, help="distinct input sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", default="compress", choices=["compress", "decode"],
+                    help="compress: the per-layer compression step (the headline); decode: append + "
+                         "decode attention over the compressed cache")
+    ap.add_argument("--budget-frac", type=float, default=None,
+                    help="decode path: keep this fraction of every prefix instead of the workload's budget")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device-to-device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -68,6 +179,8 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.path == "decode":
+        return bench_decode(args)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload, alpha=args.alpha)

@@ -73,7 +73,9 @@ __device__ __forceinline__ int rows_held(const int *cu, const int *seg_len, int 
 
 // Blocks of `split` rows per segment, summed over the segments in front of segment `s_first` of
 // this thread's run (thread t owns segments t*per .. t*per+per-1).  Returns the exclusive prefix;
-// *total gets the sum over all segments.  One call per kernel; uses sh[0..4].
+// *total gets the sum over all segments.  One call per kernel, by all NWV wavefronts of the
+// workgroup; uses sh[0..NWV-1].
+template <int NWV = 4>
 __device__ __forceinline__ int scan_blocks(int nseg, int per, int split, int headroom,
                                            const int *cu, const int *seg_len, int *sh,
                                            int *total) {
@@ -93,7 +95,7 @@ __device__ __forceinline__ int scan_blocks(int nseg, int per, int split, int hea
   __syncthreads();
   int before = 0, all = 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NWV; ++i) {
     const int v = sh[i];
     if (i < wv) before += v;
     all += v;
@@ -135,20 +137,22 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
     for (int i = 0; i < per; ++i) {
       const int s = tid * per + i;
       if (s >= nseg) break;
-      const int nb = (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
+      const int held = rows_held(cu, seg_len, s, headroom);
+      const int nb = (held + split - 1) / split;
       if ((int)blockIdx.x >= first && (int)blockIdx.x < first + nb) {
         sh_scan[4] = s;
         sh_scan[5] = (int)blockIdx.x - first;
+        sh_scan[6] = held;
+        sh_scan[7] = cu[s];
       }
       first += nb;
     }
   }
   __syncthreads();
-  const int s = sh_scan[4], j = sh_scan[5];
+  const int s = sh_scan[4], j = sh_scan[5], len = sh_scan[6];
   const int b = s / h, c = s % h;
-  const int len = rows_held(cu, seg_len, s, headroom);
   const int r0 = j * split, r1 = min(len, r0 + split);
-  const long long seg_byte = ((long long)cu[s] + (long long)s * headroom) * ROWB + col * 16;
+  const long long seg_byte = ((long long)sh_scan[7] + (long long)s * headroom) * ROWB + col * 16;
   const char *Kb = Kc + seg_byte;
   const char *Vb = Vc + seg_byte;
 
@@ -280,41 +284,75 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
   }
 }
 
-// One workgroup per segment merges that segment's splits and normalises.
+// One workgroup per (segment, query head of its group) merges that segment's splits and
+// normalises.  A long segment has hundreds of splits, so they are merged NSLOT side by side
+// (each by D/4 lanes holding a float4 of the value sum), four loads deep, then across slots.
 template <int D, int G>
-__global__ __launch_bounds__(256) void decode_combine_kernel(
+__global__ __launch_bounds__(1024) void decode_combine_kernel(
     int nseg, int h, int per, int split, int headroom, const int *__restrict__ cu,
     const int *__restrict__ seg_len, const float *__restrict__ part_acc,
     const float *__restrict__ part_ml, float *__restrict__ out, float *__restrict__ lse) {
-  __shared__ int sh_scan[8];
+  constexpr int LPE = D / 4;
+  constexpr int NSLOT = 1024 / LPE;
+  constexpr int UC = 4;
+  __shared__ int sh_scan[24];
+  __shared__ float sh_a[NSLOT][D];
+  __shared__ float sh_m[NSLOT], sh_l[NSLOT];
   const int tid = threadIdx.x;
-  const int s = blockIdx.x;
+  const int s = blockIdx.x, gi = blockIdx.y;
   int total;
-  const int excl = scan_blocks(nseg, per, split, headroom, cu, seg_len, sh_scan, &total);
+  const int excl = scan_blocks<16>(nseg, per, split, headroom, cu, seg_len, sh_scan, &total);
   if (s >= tid * per && s < tid * per + per) {
     int first = excl;
     for (int i = 0; tid * per + i < s; ++i)
       first += (rows_held(cu, seg_len, tid * per + i, headroom) + split - 1) / split;
-    sh_scan[4] = first;
+    sh_scan[16] = first;
+    sh_scan[17] = (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
   }
   __syncthreads();
-  const int p0 = sh_scan[4];
-  const int cnt = (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
-  const int b = s / h, c = s % h;
-  for (int t = tid; t < G * D; t += 256) {
-    const int gi = t / D, e = t % D;
-    float M = M_INIT;
-    for (int p = 0; p < cnt; ++p) M = fmaxf(M, part_ml[((long long)(p0 + p) * G + gi) * 2]);
-    float a = 0.0f, ll = 0.0f;
-    for (int p = 0; p < cnt; ++p) {
-      const long long pg = (long long)(p0 + p) * G + gi;
-      const float f = fast_exp2(part_ml[pg * 2] - M);
-      a = fmaf(part_acc[pg * D + e], f, a);
-      ll = fmaf(part_ml[pg * 2 + 1], f, ll);
+  const int p0 = sh_scan[16], cnt = sh_scan[17];
+  const int e4 = tid % LPE, slot = tid / LPE;
+
+  float m = M_INIT, l = 0.0f;
+  float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  for (int p = slot; p < cnt; p += NSLOT * UC) {
+    float2 ml[UC];
+    float4 pa[UC];
+#pragma unroll
+    for (int u = 0; u < UC; ++u) {
+      const int pp = p + u * NSLOT;
+      const long long pg = (long long)(p0 + (pp < cnt ? pp : p)) * G + gi;
+      ml[u] = *reinterpret_cast<const float2 *>(part_ml + pg * 2);
+      pa[u] = *reinterpret_cast<const float4 *>(part_acc + pg * D + e4 * 4);
+      if (pp >= cnt) { ml[u] = make_float2(M_INIT, 0.0f); pa[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f); }
     }
-    const long long row = (long long)(b * h + c) * G + gi;
-    out[row * D + e] = ll > 0.0f ? a / ll : 0.0f;
-    if (lse && e == 0) lse[row] = ll > 0.0f ? (M + log2f(ll)) * LN2 : -INFINITY;
+#pragma unroll
+    for (int u = 0; u < UC; ++u) {
+      const float mn = fmaxf(m, ml[u].x);
+      const float fo = fast_exp2(m - mn), fn = fast_exp2(ml[u].x - mn);
+      l = l * fo + ml[u].y * fn;
+      a.x = a.x * fo + pa[u].x * fn; a.y = a.y * fo + pa[u].y * fn;
+      a.z = a.z * fo + pa[u].z * fn; a.w = a.w * fo + pa[u].w * fn;
+      m = mn;
+    }
+  }
+  *reinterpret_cast<float4 *>(&sh_a[slot][e4 * 4]) = a;
+  if (e4 == 0) { sh_m[slot] = m; sh_l[slot] = l; }
+  __syncthreads();
+  if (tid < D) {
+    float M = sh_m[0];
+#pragma unroll
+    for (int k = 1; k < NSLOT; ++k) M = fmaxf(M, sh_m[k]);
+    float acc = 0.0f, ll = 0.0f;
+#pragma unroll 8
+    for (int k = 0; k < NSLOT; ++k) {
+      const float f = fast_exp2(sh_m[k] - M);
+      acc = fmaf(sh_a[k][tid], f, acc);
+      ll = fmaf(sh_l[k], f, ll);
+    }
+    const long long row = (long long)s * G + gi;       // = (b*h + c)*G + gi
+    out[row * D + tid] = ll > 0.0f ? acc / ll : 0.0f;
+    if (lse && tid == 0) lse[row] = ll > 0.0f ? (M + log2f(ll)) * LN2 : -INFINITY;
   }
 }
 
@@ -352,7 +390,7 @@ void run_decode(const SeqTab &st, const Dims &dm, int headroom, const DecodePlan
   ADAKV_LAUNCH("decode_attn", (decode_attn_kernel<T, D, G>), dim3(pl.nblk), dim3(256), s, nseg,
                dm.h_kv, per, pl.split, headroom, dm.scale * LOG2E, (const T *)q, cu, seg_len,
                (const char *)Kc, (const char *)Vc, part_acc, part_ml);
-  ADAKV_LAUNCH("decode_combine", (decode_combine_kernel<D, G>), dim3(nseg), dim3(256), s, nseg,
+  ADAKV_LAUNCH("decode_combine", (decode_combine_kernel<D, G>), dim3(nseg, G), dim3(1024), s, nseg,
                dm.h_kv, per, pl.split, headroom, cu, seg_len, (const float *)part_acc,
                (const float *)part_ml, out, lse);
 }
@@ -381,8 +419,14 @@ DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom) {
   const long long nseg = (long long)st.batch * dm.h_kv;
   const long long cap = (long long)st.out_off[st.batch] + nseg * headroom;
   // rows per workgroup: as long as possible while about a thousand workgroups remain
-  int split = 1024;
-  while (split > 64 && cap / split < 1024) split >>= 1;
+#ifndef ADAKV_DECODE_TARGET_WGS
+#define ADAKV_DECODE_TARGET_WGS 1024
+#endif
+#ifndef ADAKV_DECODE_MAX_SPLIT
+#define ADAKV_DECODE_MAX_SPLIT 1024
+#endif
+  int split = ADAKV_DECODE_MAX_SPLIT;
+  while (split > 64 && cap / split < ADAKV_DECODE_TARGET_WGS) split >>= 1;
   pl.split = split;
   pl.nblk = (int)(cap / split + nseg);          // >= sum over segments of ceil(len / split)
   pl.part_acc = 0;
