@@ -8,7 +8,7 @@ distinct input sets (more than a gigabyte in total, against 256 MB of memory-sid
 that the K stream really comes from HBM.
 
 `--path decode` measures the decode side of the flattened cache instead (one step = one
-adakv_append + one adakv_decode_attn over the layer's compressed cache, built by the same
+adakv_decode_step, i.e. append + decode attention, over the layer's compressed cache, built by the same
 compression with `--budget-frac` of every prefix kept); the default is the compression step.
 
 Prints ONE JSON line.  `value` is prefix tokens compressed per second (the layer's n divided
@@ -48,8 +48,8 @@ def algorithmic_bytes(wl, kept_rows):
 
 
 def bench_decode(args):
-    """One step = adakv_append + adakv_decode_attn for every sequence and head of one layer, on
-    the cache the compression step produced."""
+    """One step = adakv_decode_step (append + attention) for every sequence and head of one
+    layer, on the cache the compression step produced."""
     import numpy as np
     import torch
 
@@ -63,7 +63,7 @@ def bench_decode(args):
         wl.B = [wl.h_kv * (wl.w + max(1, int(round(args.budget_frac * nb)))) for nb in wl.n]
     layer = adakv.Layer.from_workload(wl)
     trace_steps = min(args.steps, 50)
-    hr = args.warmup + args.steps + trace_steps
+    hr = args.warmup + args.steps + trace_steps + 2
     sets = []
     for i in range(args.sets):
         q, K, V = synth.generate(wl, layer=i, device=dev)
@@ -82,8 +82,8 @@ def bench_decode(args):
     def step(i):
         Kc, Vc, cu, seg_len = sets[i % len(sets)]
         t = i % nsteps
-        adakv.append(layer, kn[t], vn[t], cu, hr, Kc, Vc, seg_len, overflow=overflow)
-        adakv.decode_attn(layer, qn[t], cu, hr, Kc, Vc, seg_len, out=out, ws=ws)
+        adakv.decode_step(layer, qn[t], kn[t], vn[t], cu, hr, Kc, Vc, seg_len, overflow=overflow,
+                          out=out, ws=ws)
 
     for i in range(args.warmup):
         step(i)
@@ -95,9 +95,10 @@ def bench_decode(args):
     t1 = time.perf_counter()
     ms_per_step = 1000.0 * (t1 - t0) / args.steps
     per_kernel, order, gaps = {}, [], []
-    for i in range(trace_steps):
-        with adakv.KernelTrace(16) as tr:
+    for i in range(0, trace_steps, 2):              # two calls per trace: the gap between them
+        with adakv.KernelTrace(16) as tr:           # is what the markers themselves cost
             step(i)
+            step(i + 1)
         torch.cuda.synchronize()
         for name, us in tr.durations_us():
             if name not in per_kernel:

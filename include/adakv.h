@@ -228,6 +228,18 @@ int adakv_decode_attn(const adakv_layer *L, const void *q_new, const int32_t *cu
                       void *hip_stream);
 
 /*
+ * adakv_append followed by adakv_decode_attn in one call (one kernel launch fewer per decoding
+ * step, and the new row is not read back from memory): every segment with room takes
+ * k_new[b][c], v_new[b][c] as its next row, attention runs over the rows including it, and
+ * seg_len[s] grows by one when the call's last kernel ends.  A full segment is attended as it
+ * is, keeps its length, and sets *overflow to 1.  Arguments as for the two calls.
+ */
+int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new,
+                      const void *v_new, const int32_t *cu_seqlens, int32_t headroom,
+                      void *K_cache, void *V_cache, int32_t *seg_len, int32_t *overflow,
+                      float *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Profiling aid for benchmarks (no part of the method).  While armed, on the arming host thread,
  * the library records the caller's events, in order, on the call's stream: one in front of every
  * kernel it launches and one at the end of every ABI call, until the array is used up.  Event i

@@ -1,10 +1,10 @@
 """MI355X-native Ada-KV per-layer cache compression: score, allocate, select, compact.
 
-Decode side of the resulting flattened cache: cache_build, append, decode_attn.
+Decode side of the resulting flattened cache: cache_build, append, decode_attn, decode_step.
 All calls run entirely in the HIP library (csrc/); this package only marshals
 arguments.  Importing the package does not load the library; the first call does,
 and raises if the library has not been built.
 """
 from .binding import (AdaKVError, KernelTrace, Layer, allocate, append, cache_build, cache_rows,  # noqa: F401
-                      compact, compress, decode_attn, decode_workspace_bytes, library_path,
+                      compact, compress, decode_attn, decode_step, decode_workspace_bytes, library_path,
                       load_library, score, select, workspace_bytes)

@@ -68,7 +68,8 @@ def load_library():
     I = ctypes.c_int32
     for name, args in (("adakv_cache_build", [P, V, V, V, V, I, V, V, V, V]),
                        ("adakv_append", [P, V, V, V, I, V, V, V, V, V]),
-                       ("adakv_decode_attn", [P, V, V, I, V, V, V, V, V, V, Z, V])):
+                       ("adakv_decode_attn", [P, V, V, I, V, V, V, V, V, V, Z, V]),
+                       ("adakv_decode_step", [P, V, V, V, V, I, V, V, V, V, V, V, V, Z, V])):
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = args
@@ -313,6 +314,41 @@ def decode_attn(layer: Layer, q_new, cu_seqlens, headroom, K_cache, V_cache, seg
                                _stream(stream))
     if st != 0:
         raise AdaKVError(st, "adakv_decode_attn")
+    return (out, lse) if (want_lse or lse is not None) else out
+
+
+def decode_step(layer: Layer, q_new, k_new, v_new, cu_seqlens, headroom, K_cache, V_cache, seg_len,
+                overflow=None, out=None, lse=None, ws=None, stream=None, want_lse=False):
+    """adakv_decode_step: append k_new/v_new to every segment and attend, in one call."""
+    lib = load_library()
+    want = (layer.batch, layer.h_q, layer.d)
+    wkv = (layer.batch, layer.h_kv, layer.d)
+    if tuple(q_new.shape) != want or not q_new.is_contiguous():
+        raise ValueError(f"q_new must be contiguous {want}")
+    if tuple(k_new.shape) != wkv or tuple(v_new.shape) != wkv or not (k_new.is_contiguous() and v_new.is_contiguous()):
+        raise ValueError(f"k_new and v_new must be contiguous {wkv}")
+    if K_cache.shape[0] < cache_rows(layer, headroom) or V_cache.shape[0] < cache_rows(layer, headroom):
+        raise ValueError("cache too small for this layer and head-room")
+    if out is None:
+        out = torch.empty(want, dtype=torch.float32, device=q_new.device)
+    if lse is None and want_lse:
+        lse = torch.empty(want[:2], dtype=torch.float32, device=q_new.device)
+    if ws is None:
+        ws = torch.empty(max(decode_workspace_bytes(layer, headroom), 16), dtype=torch.uint8,
+                         device=q_new.device)
+    st = lib.adakv_decode_step(ctypes.byref(layer.c), _ptr(q_new, "q_new", layer.torch_dtype),
+                               _ptr(k_new, "k_new", layer.torch_dtype),
+                               _ptr(v_new, "v_new", layer.torch_dtype),
+                               _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(headroom),
+                               _ptr(K_cache, "K_cache", layer.torch_dtype),
+                               _ptr(V_cache, "V_cache", layer.torch_dtype),
+                               _ptr(seg_len, "seg_len", torch.int32),
+                               _ptr(overflow, "overflow", torch.int32),
+                               _ptr(out, "out", torch.float32), _ptr(lse, "lse", torch.float32),
+                               ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel()),
+                               _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_decode_step")
     return (out, lse) if (want_lse or lse is not None) else out
 
 

@@ -244,8 +244,33 @@ int adakv_decode_attn(const adakv_layer *L, const void *q_new, const int32_t *cu
   if (!aligned16(q_new) || !aligned16(K_cache) || !aligned16(V_cache)) return ADAKV_EUNSUPPORTED;
   if (!ws || ws_bytes < plan_decode(st, dm, headroom).total + 256) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
-  hipError_t e = launch_decode_attn(st, dm, L->dtype, headroom, q_new, cu_seqlens, K_cache,
-                                    V_cache, seg_len, out, lse, wsp, (hipStream_t)hip_stream);
+  hipError_t e = launch_decode_attn(st, dm, L->dtype, headroom, q_new, nullptr, nullptr,
+                                    cu_seqlens, (void *)K_cache, (void *)V_cache,
+                                    (int *)seg_len, nullptr, out, lse, wsp,
+                                    (hipStream_t)hip_stream);
+  trace_mark((hipStream_t)hip_stream, "end");
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new,
+                      const void *v_new, const int32_t *cu_seqlens, int32_t headroom,
+                      void *K_cache, void *V_cache, int32_t *seg_len, int32_t *overflow,
+                      float *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if ((rc = check_headroom(st, dm, headroom)) != ADAKV_OK) return rc;
+  if (!q_new || !k_new || !v_new || !cu_seqlens || !K_cache || !V_cache || !seg_len || !out)
+    return ADAKV_EINVAL;
+  if (!decode_supported(dm)) return ADAKV_EUNSUPPORTED;
+  if (!aligned16(q_new) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(K_cache) ||
+      !aligned16(V_cache))
+    return ADAKV_EUNSUPPORTED;
+  if (!ws || ws_bytes < plan_decode(st, dm, headroom).total + 256) return ADAKV_EWORKSPACE;
+  char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
+  hipError_t e = launch_decode_attn(st, dm, L->dtype, headroom, q_new, k_new, v_new, cu_seqlens,
+                                    K_cache, V_cache, seg_len, overflow, out, lse, wsp,
+                                    (hipStream_t)hip_stream);
   trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }

@@ -88,14 +88,16 @@ hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const voi
 struct DecodePlan {
   int split;                        // rows of a segment per workgroup
   int nblk;                         // workgroups launched: an upper bound on what the lengths need
-  size_t part_acc, part_ml, total;  // byte offsets of the per-workgroup partial results
+  size_t part_acc, part_ml;         // byte offsets of the per-workgroup partial results
+  size_t seg_tab, total;            // per segment: first partial, partials, rows, appended
 };
 bool decode_supported(const Dims &dm);
 DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom);
+// k_new == nullptr: attention only (cache and lengths are only read)
 hipError_t launch_decode_attn(const SeqTab &st, const Dims &dm, int dtype, int headroom,
-                              const void *q, const int *cu, const void *Kc, const void *Vc,
-                              const int *seg_len, float *out, float *lse, char *ws,
-                              hipStream_t s);
+                              const void *q, const void *k_new, const void *v_new, const int *cu,
+                              void *Kc, void *Vc, int *seg_len, int *overflow, float *out,
+                              float *lse, char *ws, hipStream_t s);
 hipError_t launch_append(const SeqTab &st, const Dims &dm, int dtype, int headroom,
                          const void *k_new, const void *v_new, const int *cu, void *Kc, void *Vc,
                          int *seg_len, int *overflow, hipStream_t s);

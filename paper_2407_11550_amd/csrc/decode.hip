@@ -66,9 +66,13 @@ template <> struct Elem<float> {
   }
 };
 
-__device__ __forceinline__ int rows_held(const int *cu, const int *seg_len, int s, int headroom) {
+// Rows of segment s this call works on: the rows held, plus the row the call itself appends
+// (`grow` = 1) if the segment has room for it.
+__device__ __forceinline__ int rows_held(const int *cu, const int *seg_len, int s, int headroom,
+                                         int grow) {
   const int cap = cu[s + 1] - cu[s] + headroom;
-  return min(max(seg_len[s], 0), cap);         // a corrupt length can never leave the segment
+  const int held = min(max(seg_len[s], 0), cap);   // a corrupt length can never leave the segment
+  return held + (held < cap ? grow : 0);
 }
 
 // Blocks of `split` rows per segment, summed over the segments in front of segment `s_first` of
@@ -76,14 +80,14 @@ __device__ __forceinline__ int rows_held(const int *cu, const int *seg_len, int 
 // *total gets the sum over all segments.  One call per kernel, by all NWV wavefronts of the
 // workgroup; uses sh[0..NWV-1].
 template <int NWV = 4>
-__device__ __forceinline__ int scan_blocks(int nseg, int per, int split, int headroom,
+__device__ __forceinline__ int scan_blocks(int nseg, int per, int split, int headroom, int grow,
                                            const int *cu, const int *seg_len, int *sh,
                                            int *total) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int mine = 0;
   for (int i = 0; i < per; ++i) {
     const int s = tid * per + i;
-    if (s < nseg) mine += (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
+    if (s < nseg) mine += (rows_held(cu, seg_len, s, headroom, grow) + split - 1) / split;
   }
   int inc = mine;
 #pragma unroll
@@ -108,8 +112,9 @@ __device__ __forceinline__ int scan_blocks(int nseg, int per, int split, int hea
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void decode_attn_kernel(
     int nseg, int h, int per, int split, int headroom, float c_log2, const T *__restrict__ q,
-    const int *__restrict__ cu, const int *__restrict__ seg_len, const char *__restrict__ Kc,
-    const char *__restrict__ Vc, float *__restrict__ part_acc, float *__restrict__ part_ml) {
+    const char *__restrict__ k_new, const char *__restrict__ v_new, const int *__restrict__ cu,
+    const int *__restrict__ seg_len, char *Kc, char *Vc, float *__restrict__ part_acc,
+    float *__restrict__ part_ml, int4 *__restrict__ seg_tab) {
   constexpr int EPL = Elem<T>::EPL;
   constexpr int ROWB = D * (int)sizeof(T);
   constexpr int LPR = ROWB / 16;               // lanes per row
@@ -120,7 +125,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
   constexpr bool PACKQ = G * EPL > 32;
   constexpr int U = PACKQ ? 2 : 4;             // row loads in flight per lane, for K and for V
 
-  __shared__ int sh_scan[8];
+  __shared__ int sh_scan[12];
   __shared__ float sh_acc[NW][G][D];
   __shared__ float sh_m[NW][G], sh_l[NW][G];
 
@@ -129,32 +134,42 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
   const int col = lane % LPR, slot = lane / LPR;
 
   // ---- which (segment, split) is this workgroup? -------------------------------------------
+  // With k_new/v_new the call appends one row per segment (Eq. 1) and attends over it as well:
+  // the row is taken from k_new/v_new by the lanes it falls to, which also store it in the cache.
+  const int grow = k_new != nullptr ? 1 : 0;
   int total;
-  const int excl = scan_blocks(nseg, per, split, headroom, cu, seg_len, sh_scan, &total);
-  if ((int)blockIdx.x >= total) return;        // uniform: the launch is an upper bound
+  const int excl = scan_blocks(nseg, per, split, headroom, grow, cu, seg_len, sh_scan, &total);
   {
     int first = excl;
     for (int i = 0; i < per; ++i) {
       const int s = tid * per + i;
       if (s >= nseg) break;
-      const int held = rows_held(cu, seg_len, s, headroom);
-      const int nb = (held + split - 1) / split;
+      const int now = rows_held(cu, seg_len, s, headroom, grow);
+      const int nb = (now + split - 1) / split;
       if ((int)blockIdx.x >= first && (int)blockIdx.x < first + nb) {
         sh_scan[4] = s;
         sh_scan[5] = (int)blockIdx.x - first;
-        sh_scan[6] = held;
+        sh_scan[6] = now;
         sh_scan[7] = cu[s];
+        sh_scan[8] = now - rows_held(cu, seg_len, s, headroom, 0);   // 1: the last row is the new one
       }
+      // the merge kernel finds a segment's partial results through this table; the launch has at
+      // least one workgroup per segment, and workgroup s files the entry of segment s
+      if (s == (int)blockIdx.x)
+        seg_tab[s] = make_int4(first, nb, now, now - rows_held(cu, seg_len, s, headroom, 0));
       first += nb;
     }
   }
+  if ((int)blockIdx.x >= total) return;        // uniform: the launch is an upper bound
   __syncthreads();
   const int s = sh_scan[4], j = sh_scan[5], len = sh_scan[6];
   const int b = s / h, c = s % h;
   const int r0 = j * split, r1 = min(len, r0 + split);
+  const int new_row = sh_scan[8] ? len - 1 : -1;
   const long long seg_byte = ((long long)sh_scan[7] + (long long)s * headroom) * ROWB + col * 16;
-  const char *Kb = Kc + seg_byte;
-  const char *Vb = Vc + seg_byte;
+  char *Kb = Kc + seg_byte;
+  char *Vb = Vc + seg_byte;
+  const long long new_byte = (long long)s * ROWB + col * 16;
 
   // ---- the g query rows of this KV head, pre-scaled so that exp() becomes exp2() --------------
   float qf[PACKQ ? 1 : G][EPL];
@@ -189,9 +204,17 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
     for (int u = 0; u < U; ++u) {
       const int r = r0 + ((it * U + u) * NW + wv) * RPW + slot;
       ok[u] = r < r1;
-      const long long o = (long long)min(r, r1 - 1) * ROWB;    // r1 >= 1: the block exists
-      kk[u] = *reinterpret_cast<const u32x4 *>(Kb + o);
-      vv[u] = *reinterpret_cast<const u32x4 *>(Vb + o);
+      const int rr = min(r, r1 - 1);                           // r1 >= 1: the block exists
+      const long long o = (long long)rr * ROWB;
+      // lanes past the end re-read the block's last row (and ignore it): if that is the new row,
+      // they too must take it from k_new/v_new, its place in the cache is not written yet
+      const bool fresh = rr == new_row;
+      kk[u] = *reinterpret_cast<const u32x4 *>(fresh ? k_new + new_byte : Kb + o);
+      vv[u] = *reinterpret_cast<const u32x4 *>(fresh ? v_new + new_byte : Vb + o);
+      if (r == new_row) {
+        *reinterpret_cast<u32x4 *>(Kb + o) = kk[u];
+        *reinterpret_cast<u32x4 *>(Vb + o) = vv[u];
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -289,28 +312,22 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
 // (each by D/4 lanes holding a float4 of the value sum), four loads deep, then across slots.
 template <int D, int G>
 __global__ __launch_bounds__(1024) void decode_combine_kernel(
-    int nseg, int h, int per, int split, int headroom, const int *__restrict__ cu,
-    const int *__restrict__ seg_len, const float *__restrict__ part_acc,
-    const float *__restrict__ part_ml, float *__restrict__ out, float *__restrict__ lse) {
+    const int4 *__restrict__ seg_tab, int *__restrict__ seg_len, int *__restrict__ overflow,
+    const float *__restrict__ part_acc, const float *__restrict__ part_ml,
+    float *__restrict__ out, float *__restrict__ lse) {
   constexpr int LPE = D / 4;
   constexpr int NSLOT = 1024 / LPE;
   constexpr int UC = 4;
-  __shared__ int sh_scan[24];
   __shared__ float sh_a[NSLOT][D];
   __shared__ float sh_m[NSLOT], sh_l[NSLOT];
   const int tid = threadIdx.x;
   const int s = blockIdx.x, gi = blockIdx.y;
-  int total;
-  const int excl = scan_blocks<16>(nseg, per, split, headroom, cu, seg_len, sh_scan, &total);
-  if (s >= tid * per && s < tid * per + per) {
-    int first = excl;
-    for (int i = 0; tid * per + i < s; ++i)
-      first += (rows_held(cu, seg_len, tid * per + i, headroom) + split - 1) / split;
-    sh_scan[16] = first;
-    sh_scan[17] = (rows_held(cu, seg_len, s, headroom) + split - 1) / split;
+  const int4 ent = seg_tab[s];                 // first partial, partials, rows now, 1 if a row was appended
+  const int p0 = ent.x, cnt = ent.y;
+  if (seg_len && gi == 0 && tid == 0) {        // the call appended: the new lengths become visible
+    if (ent.w) seg_len[s] = ent.z;
+    else if (overflow) *overflow = 1;          // the segment was full, its new row was dropped
   }
-  __syncthreads();
-  const int p0 = sh_scan[16], cnt = sh_scan[17];
   const int e4 = tid % LPE, slot = tid / LPE;
 
   float m = M_INIT, l = 0.0f;
@@ -381,31 +398,47 @@ __global__ __launch_bounds__(256) void append_kernel(
 
 template <typename T, int D, int G>
 void run_decode(const SeqTab &st, const Dims &dm, int headroom, const DecodePlan &pl,
-                const void *q, const int *cu, const void *Kc, const void *Vc, const int *seg_len,
-                float *out, float *lse, char *ws, hipStream_t s) {
+                const void *q, const void *k_new, const void *v_new, const int *cu, void *Kc,
+                void *Vc, int *seg_len, int *overflow, float *out, float *lse, char *ws,
+                hipStream_t s) {
   const int nseg = st.batch * dm.h_kv;
   const int per = (nseg + 255) / 256;
   float *part_acc = (float *)(ws + pl.part_acc);
   float *part_ml = (float *)(ws + pl.part_ml);
+  int4 *seg_tab = (int4 *)(ws + pl.seg_tab);
   ADAKV_LAUNCH("decode_attn", (decode_attn_kernel<T, D, G>), dim3(pl.nblk), dim3(256), s, nseg,
-               dm.h_kv, per, pl.split, headroom, dm.scale * LOG2E, (const T *)q, cu, seg_len,
-               (const char *)Kc, (const char *)Vc, part_acc, part_ml);
-  ADAKV_LAUNCH("decode_combine", (decode_combine_kernel<D, G>), dim3(nseg, G), dim3(1024), s, nseg,
-               dm.h_kv, per, pl.split, headroom, cu, seg_len, (const float *)part_acc,
+               dm.h_kv, per, pl.split, headroom, dm.scale * LOG2E, (const T *)q,
+               (const char *)k_new, (const char *)v_new, cu, (const int *)seg_len, (char *)Kc,
+               (char *)Vc, part_acc, part_ml, seg_tab);
+  // only a call that appends hands the lengths to the merge kernel for updating
+  ADAKV_LAUNCH("decode_combine", (decode_combine_kernel<D, G>), dim3(nseg, G), dim3(1024), s,
+               (const int4 *)seg_tab, k_new ? seg_len : nullptr, overflow, (const float *)part_acc,
                (const float *)part_ml, out, lse);
 }
 
+struct DecodeArgs {
+  const void *q, *k_new, *v_new;
+  const int *cu;
+  void *Kc, *Vc;
+  int *seg_len, *overflow;
+  float *out, *lse;
+  char *ws;
+};
+
 template <typename T, int D>
 bool run_decode_g(const SeqTab &st, const Dims &dm, int headroom, const DecodePlan &pl,
-                  const void *q, const int *cu, const void *Kc, const void *Vc,
-                  const int *seg_len, float *out, float *lse, char *ws, hipStream_t s) {
+                  const DecodeArgs &a, hipStream_t s) {
+#define ADAKV_DECODE_G(G)                                                                       \
+  run_decode<T, D, G>(st, dm, headroom, pl, a.q, a.k_new, a.v_new, a.cu, a.Kc, a.Vc, a.seg_len,   \
+                      a.overflow, a.out, a.lse, a.ws, s)
   switch (dm.g) {
-    case 1: run_decode<T, D, 1>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
-    case 2: run_decode<T, D, 2>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
-    case 4: run_decode<T, D, 4>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
-    case 8: run_decode<T, D, 8>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s); return true;
+    case 1: ADAKV_DECODE_G(1); return true;
+    case 2: ADAKV_DECODE_G(2); return true;
+    case 4: ADAKV_DECODE_G(4); return true;
+    case 8: ADAKV_DECODE_G(8); return true;
     default: return false;
   }
+#undef ADAKV_DECODE_G
 }
 
 }  // namespace
@@ -431,22 +464,24 @@ DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom) {
   pl.nblk = (int)(cap / split + nseg);          // >= sum over segments of ceil(len / split)
   pl.part_acc = 0;
   pl.part_ml = align_up((size_t)pl.nblk * dm.g * dm.d * sizeof(float), 256);
-  pl.total = pl.part_ml + align_up((size_t)pl.nblk * dm.g * 2 * sizeof(float), 256);
+  pl.seg_tab = pl.part_ml + align_up((size_t)pl.nblk * dm.g * 2 * sizeof(float), 256);
+  pl.total = pl.seg_tab + align_up((size_t)nseg * sizeof(int4), 256);
   return pl;
 }
 
 hipError_t launch_decode_attn(const SeqTab &st, const Dims &dm, int dtype, int headroom,
-                              const void *q, const int *cu, const void *Kc, const void *Vc,
-                              const int *seg_len, float *out, float *lse, char *ws,
-                              hipStream_t s) {
+                              const void *q, const void *k_new, const void *v_new, const int *cu,
+                              void *Kc, void *Vc, int *seg_len, int *overflow, float *out,
+                              float *lse, char *ws, hipStream_t s) {
   const DecodePlan pl = plan_decode(st, dm, headroom);
+  const DecodeArgs a = {q, k_new, v_new, cu, Kc, Vc, seg_len, overflow, out, lse, ws};
   bool ok;
   if (dtype == ADAKV_BF16) {
-    ok = dm.d == 64 ? run_decode_g<unsigned short, 64>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s)
-                    : run_decode_g<unsigned short, 128>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s);
+    ok = dm.d == 64 ? run_decode_g<unsigned short, 64>(st, dm, headroom, pl, a, s)
+                    : run_decode_g<unsigned short, 128>(st, dm, headroom, pl, a, s);
   } else {
-    ok = dm.d == 64 ? run_decode_g<float, 64>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s)
-                    : run_decode_g<float, 128>(st, dm, headroom, pl, q, cu, Kc, Vc, seg_len, out, lse, ws, s);
+    ok = dm.d == 64 ? run_decode_g<float, 64>(st, dm, headroom, pl, a, s)
+                    : run_decode_g<float, 128>(st, dm, headroom, pl, a, s);
   }
   if (!ok) return hipErrorInvalidValue;
   return hipGetLastError();

@@ -169,6 +169,48 @@ def test_append_then_attend_matches_oracle_step_by_step_and_reports_overflow():
     assert (olen == (cu[1:] - cu[:-1]) + hr).all()               # every segment ended up full
 
 
+@pytest.mark.parametrize("case", [
+    # h_q h_kv d   w  n           B per head  dtype          headroom steps
+    (8, 2, 128, 8, [700, 300], [90, 40], torch.bfloat16, 3, 5),      # runs into full segments
+    (32, 8, 128, 32, [4000], [160], torch.bfloat16, 70, 70),         # lengths cross a 64-row split boundary
+    (4, 4, 64, 4, [500], [36], torch.float32, 4, 4),
+], ids=["overflow", "split_boundary", "fp32"])
+def test_fused_step_equals_append_then_attend(case):
+    h_q, h, d, w, n, Bh, dt, hr, steps = case
+    _say(f"fused decode step {case}")
+    wl = synth.small_workload(h_q, h, d, w, 7, n, [h * b for b in Bh], dtype=dt, seed=17)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl)
+    res = adakv.compress(layer, q, K, V)
+    rows = adakv.cache_rows(layer, hr)
+    Kc = torch.full((rows, wl.d), float("nan"), dtype=wl.dtype, device=DEV)   # spare rows must never be read
+    Vc = torch.full((rows, wl.d), float("nan"), dtype=wl.dtype, device=DEV)
+    _, _, seg_len = adakv.cache_build(layer, K, V, res["indices"], res["cu_seqlens"], hr, Kc, Vc)
+    overflow = torch.zeros(1, dtype=torch.int32, device=DEV)
+    torch.cuda.synchronize()
+    cu = res["cu_seqlens"].cpu().numpy()
+    oK, oV, olen = to_f64(Kc), to_f64(Vc), seg_len.cpu().numpy().astype(np.int64)
+    qn, kn, vn = synth.decode_inputs(wl, steps, seed=17, device=DEV)
+    ws = torch.empty(adakv.decode_workspace_bytes(layer, hr), dtype=torch.uint8, device=DEV)
+    vmax = float(V.float().abs().max())
+    start = D.segment_starts(cu, hr)
+    any_full = False
+    for t in range(steps):
+        out, lse = adakv.decode_step(layer, qn[t], kn[t], vn[t], res["cu_seqlens"], hr, Kc, Vc, seg_len,
+                                     overflow=overflow, ws=ws, want_lse=True)
+        torch.cuda.synchronize()
+        any_full |= D.append(oK, oV, cu, hr, olen, to_f64(kn[t]).reshape(-1, wl.d), to_f64(vn[t]).reshape(-1, wl.d))
+        assert np.array_equal(seg_len.cpu().numpy(), olen), t
+        assert bool(overflow.item()) == any_full, t
+        if t % 7 == 0 or t == steps - 1:
+            gK, gV = to_f64(Kc), to_f64(Vc)
+            for s in range(len(olen)):
+                assert np.array_equal(gK[start[s]:start[s] + olen[s]], oK[start[s]:start[s] + olen[s]])
+                assert np.array_equal(gV[start[s]:start[s] + olen[s]], oV[start[s]:start[s] + olen[s]])
+        ref_out, ref_lse = D.decode_attention(to_f64(qn[t]), np.nan_to_num(oK), np.nan_to_num(oV), cu, hr, olen, wl.g)
+        _assert_decode_close(out, lse, ref_out, ref_lse, vmax, f"step {t}")
+
+
 def test_decode_rejects_bad_arguments():
     _say("decode argument checks")
     wl = synth.small_workload(6, 2, 128, 4, 7, [100], [2 * 20], seed=1)      # g = 3: not supported
