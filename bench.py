@@ -12,9 +12,10 @@ adakv_decode_step, i.e. append + decode attention, over the layer's compressed c
 compression with `--budget-frac` of every prefix kept); the default is the compression step.
 
 Prints ONE JSON line.  `value` is prefix tokens compressed per second (the layer's n divided
-by the time of a step).  `roofline` describes the dominant kernel, timed live with events
-recorded in front of and behind it on the launch stream (adakv_trace_arm) in a second pass
-over the same inputs; `cpu_baseline` is the fp64 CPU oracle on the same layer.
+by the time of a step).  `roofline` describes the dominant kernel, timed live with a pair of
+events attached to its launch on the launch stream (adakv_trace_arm; they receive the kernel's
+own start and end time) in a second pass over the same inputs; `cpu_baseline` is the fp64 CPU
+oracle on the same layer.
 """
 import argparse
 import json
@@ -63,7 +64,7 @@ def bench_decode(args):
         wl.B = [wl.h_kv * (wl.w + max(1, int(round(args.budget_frac * nb)))) for nb in wl.n]
     layer = adakv.Layer.from_workload(wl)
     trace_steps = min(args.steps, 50)
-    hr = args.warmup + args.steps + trace_steps + 2
+    hr = args.warmup + args.steps + trace_steps
     sets = []
     for i in range(args.sets):
         q, K, V = synth.generate(wl, layer=i, device=dev)
@@ -94,30 +95,26 @@ def bench_decode(args):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = 1000.0 * (t1 - t0) / args.steps
-    per_kernel, order, gaps = {}, [], []
-    for i in range(0, trace_steps, 2):              # two calls per trace: the gap between them
-        with adakv.KernelTrace(16) as tr:           # is what the markers themselves cost
+    per_kernel, order = {}, []
+    for i in range(trace_steps):
+        with adakv.KernelTrace(16) as tr:
             step(i)
-            step(i + 1)
         torch.cuda.synchronize()
         for name, us in tr.durations_us():
             if name not in per_kernel:
                 per_kernel[name] = []
                 order.append(name)
             per_kernel[name].append(us)
-        gaps.extend(tr.marker_gaps_us())
     assert int(overflow.item()) == 0, "head-room too small for the number of steps"
     kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
-    marker_us = float(np.median(gaps)) if gaps else 0.0
     esz = 2 if str(wl.dtype).endswith("bfloat16") else 4
     rows = float(np.mean([int(s[3].sum().item()) for s in sets]))      # rows held at the end
     dom_bytes = rows * wl.d * esz * 2                                   # every K and V row once
-    dom_us = max(kernels["decode_attn"] - marker_us, 1e-3)
+    dom_us = max(kernels["decode_attn"], 1e-3)
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_attn", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes": int(dom_bytes), "avg_us": round(dom_us, 2),
-                "avg_us_between_markers": round(kernels["decode_attn"], 2), "marker_us": round(marker_us, 2)}
+                "traffic": None, "algorithmic_bytes": int(dom_bytes), "avg_us": round(dom_us, 2)}
     cpu = None
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
@@ -222,7 +219,6 @@ def main():
     # ---- per-kernel durations, live, events on the launch stream (a second pass) ------------
     per_kernel = {}
     order = []
-    gaps = []
     trace_steps = min(args.steps, 50)
     for i in range(trace_steps):
         with adakv.KernelTrace(64) as tr:
@@ -233,11 +229,7 @@ def main():
                 per_kernel[name] = []
                 order.append(name)
             per_kernel[name].append(us)
-        gaps.extend(tr.marker_gaps_us())
     kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
-    # an interval between two markers with no kernel in it: what the markers add to every
-    # bracketed kernel (rocprofv3's kernel times come out lower by about this much)
-    marker_us = float(np.median(gaps)) if gaps else 0.0
     kept = layer.num_rows_out
     alg = algorithmic_bytes(wl, kept)
     dominant = max(kernels, key=kernels.get)
@@ -248,8 +240,7 @@ def main():
         dom_bytes = alg["compact"]
     else:
         dom_bytes = tokens * wl.h_kv * 4
-    dom_us_raw = kernels[dominant]
-    dom_us = max(dom_us_raw - marker_us, 1e-3)
+    dom_us = max(kernels[dominant], 1e-3)
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     total_alg = alg["score"] + alg["allocate"] + alg["select"] + alg["compact"]
     flops = 2.0 * wl.g * wl.w * wl.d * wl.h_kv * tokens
@@ -259,8 +250,7 @@ def main():
     traffic = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant))
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic, "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2),
-                "avg_us_between_markers": round(dom_us_raw, 2), "marker_us": round(marker_us, 2)}
+                "traffic": traffic, "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
 
     # ---- the oracle on the host cores: whole layers of the same workload, about 10 s ----------
     cpu = None

@@ -241,15 +241,16 @@ int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new
 
 /*
  * Profiling aid for benchmarks (no part of the method).  While armed, on the arming host thread,
- * the library records the caller's events, in order, on the call's stream: one in front of every
- * kernel it launches and one at the end of every ABI call, until the array is used up.  Event i
- * to event i+1 therefore brackets the kernel named adakv_trace_name(i); the name "end" marks the
- * end of a call.  The extra stream markers slow the pipeline down a little, so throughput is
- * measured unarmed.
+ * every kernel the library launches carries two of the caller's events, taken from the array in
+ * order: events 2i and 2i+1 receive the start and the end timestamp of the i-th kernel itself
+ * (hipEventElapsedTime between them is that kernel's run time, without launch gaps), and
+ * adakv_trace_name(2i) names it.  When fewer than two events are left, further kernels are
+ * launched plainly.  Dispatches that carry events are ordered more strictly by the runtime, so
+ * throughput is measured unarmed.
  *
  *   events (host) array of n_events hipEvent_t handles created by the caller, which must stay
- *          alive until adakv_trace_disarm; 1 <= n_events <= ADAKV_TRACE_MAX
- * adakv_trace_disarm returns how many events were recorded; adakv_trace_name(i) is valid until
+ *          alive until adakv_trace_disarm; 2 <= n_events <= ADAKV_TRACE_MAX
+ * adakv_trace_disarm returns how many events were used; adakv_trace_name(i) is valid until
  * the next adakv_trace_arm on the same thread.
  */
 #define ADAKV_TRACE_MAX 256

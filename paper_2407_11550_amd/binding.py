@@ -354,7 +354,7 @@ def decode_step(layer: Layer, q_new, k_new, v_new, cu_seqlens, headroom, K_cache
 
 class KernelTrace:
     """Per-kernel timing through adakv_trace_arm: inside the `with` block every kernel the
-    library launches (on torch's current stream) is bracketed by events."""
+    library launches carries a pair of events that receive its own start and end time."""
 
     def __init__(self, capacity=128):
         self.events = [torch.cuda.Event(enable_timing=True) for _ in range(capacity)]
@@ -377,17 +377,7 @@ class KernelTrace:
         self.names = self.names[:self.used]
         return False
 
-    def marker_gaps_us(self):
-        """Microseconds between the marker at the end of one call and the marker in front of the
-        next call's first kernel: no kernel runs in between, so this is what the markers
-        themselves cost on the stream; call after a synchronize."""
-        return [1000.0 * self.events[i].elapsed_time(self.events[i + 1])
-                for i in range(self.used - 1) if self.names[i] == "end"]
-
     def durations_us(self):
-        """[(kernel name, microseconds)] for every bracketed kernel; call after a synchronize."""
-        out = []
-        for i in range(self.used - 1):
-            if self.names[i] != "end":
-                out.append((self.names[i], 1000.0 * self.events[i].elapsed_time(self.events[i + 1])))
-        return out
+        """[(kernel name, microseconds)] for every traced kernel; call after a synchronize."""
+        return [(self.names[i], 1000.0 * self.events[i].elapsed_time(self.events[i + 1]))
+                for i in range(0, self.used - 1, 2)]

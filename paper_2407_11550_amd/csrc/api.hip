@@ -73,11 +73,14 @@ static thread_local struct {
   const char *names[ADAKV_TRACE_MAX];
 } g_trace;
 
-void trace_mark(hipStream_t s, const char *name) {
-  if (!g_trace.events || g_trace.used >= g_trace.capacity) return;
+bool trace_pair(const char *name, hipEvent_t *start, hipEvent_t *stop) {
+  if (!g_trace.events || g_trace.used + 2 > g_trace.capacity) return false;
   g_trace.names[g_trace.used] = name;
-  (void)hipEventRecord((hipEvent_t)g_trace.events[g_trace.used], s);
-  g_trace.used += 1;
+  g_trace.names[g_trace.used + 1] = name;
+  *start = (hipEvent_t)g_trace.events[g_trace.used];
+  *stop = (hipEvent_t)g_trace.events[g_trace.used + 1];
+  g_trace.used += 2;
+  return true;
 }
 
 }  // namespace adakv
@@ -93,7 +96,7 @@ size_t adakv_workspace_bytes(const adakv_layer *L) {
 }
 
 int adakv_trace_arm(void *const *events, int n_events) {
-  if (!events || n_events < 1 || n_events > ADAKV_TRACE_MAX) return ADAKV_EINVAL;
+  if (!events || n_events < 2 || n_events > ADAKV_TRACE_MAX) return ADAKV_EINVAL;
   g_trace.events = events;
   g_trace.capacity = n_events;
   g_trace.used = 0;
@@ -137,7 +140,6 @@ int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const
                      ? launch_score_mfma(st, dm, q_window, K, row_lse, scores, wsp, pl, s)
                      : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
                                             pl, s);
-  trace_mark(s, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -151,7 +153,6 @@ int adakv_allocate(const adakv_layer *L, const float *scores, int32_t *budgets,
   if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   hipError_t e = launch_allocate(st, dm, scores, budgets, cu_seqlens, wsp, (hipStream_t)hip_stream);
-  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -167,7 +168,6 @@ int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budge
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   hipError_t e = launch_select(st, dm, scores, budgets, cu_seqlens, indices, wsp,
                                (hipStream_t)hip_stream);
-  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -181,7 +181,6 @@ int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int3
     return ADAKV_EUNSUPPORTED;
   hipError_t e = launch_compact(st, dm, L->dtype, K, V, indices, cu_seqlens, K_out, V_out, 0,
                                 nullptr, (hipStream_t)hip_stream);
-  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -204,7 +203,6 @@ int adakv_cache_build(const adakv_layer *L, const void *K, const void *V, const 
     return ADAKV_EUNSUPPORTED;
   hipError_t e = launch_compact(st, dm, L->dtype, K, V, indices, cu_seqlens, K_cache, V_cache,
                                 headroom, seg_len, (hipStream_t)hip_stream);
-  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -220,7 +218,6 @@ int adakv_append(const adakv_layer *L, const void *k_new, const void *v_new,
     return ADAKV_EUNSUPPORTED;
   hipError_t e = launch_append(st, dm, L->dtype, headroom, k_new, v_new, cu_seqlens, K_cache,
                                V_cache, seg_len, overflow, (hipStream_t)hip_stream);
-  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -248,7 +245,6 @@ int adakv_decode_attn(const adakv_layer *L, const void *q_new, const int32_t *cu
                                     cu_seqlens, (void *)K_cache, (void *)V_cache,
                                     (int *)seg_len, nullptr, out, lse, wsp,
                                     (hipStream_t)hip_stream);
-  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -271,7 +267,6 @@ int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new
   hipError_t e = launch_decode_attn(st, dm, L->dtype, headroom, q_new, k_new, v_new, cu_seqlens,
                                     K_cache, V_cache, seg_len, overflow, out, lse, wsp,
                                     (hipStream_t)hip_stream);
-  trace_mark((hipStream_t)hip_stream, "end");
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -103,18 +104,21 @@ hipError_t launch_append(const SeqTab &st, const Dims &dm, int dtype, int headro
                          int *seg_len, int *overflow, hipStream_t s);
 
 
-// Profiling aid (adakv_trace_arm): while armed on this host thread, an event is recorded on the
-// stream in front of every kernel and at the end of every ABI call.
-void trace_mark(hipStream_t s, const char *name);
+// Profiling aid (adakv_trace_arm): while armed on this host thread, every kernel launch carries
+// a pair of the caller's events that receive the kernel's own start and end timestamps.
+bool trace_pair(const char *name, hipEvent_t *start, hipEvent_t *stop);
 void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float *part_m,
                         const float *part_l, float *lse, hipStream_t s);
 void launch_pool(const SeqTab &st, const Dims &dm, const float *raw, float *scores,
                  hipStream_t s);
 
-#define ADAKV_LAUNCH(name, kernel, grid, block, stream, ...)              \
-  do {                                                                    \
-    ::adakv::trace_mark(stream, name);                                    \
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);      \
+#define ADAKV_LAUNCH(name, kernel, grid, block, stream, ...)                                   \
+  do {                                                                                         \
+    hipEvent_t ev0_, ev1_;                                                                     \
+    if (::adakv::trace_pair(name, &ev0_, &ev1_))                                               \
+      hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev0_, ev1_, 0, __VA_ARGS__);       \
+    else                                                                                       \
+      hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                         \
   } while (0)
 
 }  // namespace adakv

@@ -99,7 +99,7 @@ def test_bench_refuses_more_than_one_gpu():
 def test_trace_arm_rejects_bad_arguments(lib):
     assert lib.adakv_trace_arm(None, 4) == -1
     arr = (ctypes.c_void_p * 2)()
-    assert lib.adakv_trace_arm(arr, 0) == -1 and lib.adakv_trace_arm(arr, 100000) == -1
+    assert lib.adakv_trace_arm(arr, 1) == -1 and lib.adakv_trace_arm(arr, 100000) == -1
     assert lib.adakv_trace_disarm() == 0
 
 
