@@ -259,3 +259,14 @@ def test_kernel_trace_names_every_kernel_and_costs_nothing_when_disarmed():
     assert all(0 < us < 1e5 for _, us in tr.durations_us()) and tr.used == 2 * len(names)
     for key in ref:
         assert torch.equal(ref[key], out[key]), key
+
+
+def test_sixty_four_sequences_in_one_call():
+    """The largest batch the ABI takes: 64 short sequences of different lengths and budgets."""
+    _say("batch 64")
+    n = [130 + 53 * i for i in range(64)]
+    B = [2 * (8 + 5 + (7 * i) % 90) for i in range(64)]
+    wl = synth.small_workload(8, 2, 128, 8, 7, n, B, seed=64)
+    q, K, V = synth.generate(wl, device=DEV)
+    _, out = _run(wl, q, K, V)
+    _check_all(wl, q, K, V, out)
