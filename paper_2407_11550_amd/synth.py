@@ -218,3 +218,22 @@ def decode_inputs(wl: Workload, steps: int, seed: int = 0, device="cpu", temp: f
     k = torch.randn((steps, wl.batch, wl.h_kv, wl.d), generator=tg, dtype=torch.float32, device=dev)
     v = torch.randn((steps, wl.batch, wl.h_kv, wl.d), generator=tg, dtype=torch.float32, device=dev)
     return q.to(wl.dtype), k.to(wl.dtype), v.to(wl.dtype)
+
+
+def prefill_row_lse(wl: Workload, q, K):
+    """What a prefill attention kernel would hand over for the window rows: the natural
+    log-sum-exp of the scaled logits of window row r over every key it sees, i.e. the n prefix
+    keys and the window keys up to and including itself (causal).  [batch, h_q, w] float32 on
+    q's device.  Input preparation only (the scoring call takes it as `row_lse`)."""
+    scale = 1.0 / math.sqrt(wl.d)
+    off = wl.tok_off
+    out = torch.empty((wl.batch, wl.h_q, wl.w), dtype=torch.float32, device=q.device)
+    causal = torch.tril(torch.ones((wl.w, wl.w), dtype=torch.bool, device=q.device))
+    for b, nb in enumerate(wl.n):
+        for c in range(wl.h_kv):
+            Kc = K[off[b]:off[b + 1], c, :].float()                         # [n + w, d]
+            qg = q[b, c * wl.g:(c + 1) * wl.g].float()                      # [g, w, d]
+            logit = torch.matmul(qg, Kc.t()) * scale                        # [g, w, n + w]
+            logit[:, :, nb:] = logit[:, :, nb:].masked_fill(~causal, float("-inf"))
+            out[b, c * wl.g:(c + 1) * wl.g] = torch.logsumexp(logit, dim=-1)
+    return out

@@ -143,3 +143,21 @@ def test_decode_side_argument_checks(lib):
     L3 = _layer(h_q=24)
     assert lib.adakv_decode_attn(ctypes.byref(L3.c), one, one, 4, one, one, one, one, None, one, 1 << 30, None) == -2
     assert adakv.cache_rows(L, 5) == L.num_rows_out + L.num_segments * 5
+
+
+def test_generated_prefill_lse_is_the_prefix_plus_window_normaliser():
+    """synth.prefill_row_lse must be the log of the denominator the oracle's
+    norm="prefix+window" uses: scores from the one equal scores from the other."""
+    import numpy as np
+    from oracle import adakv_oracle as O
+    from paper_2407_11550_amd import synth
+    wl = synth.small_workload(4, 2, 64, 5, 3, [70, 33], [2 * 12, 2 * 9], dtype=torch.float32, seed=4)
+    q, K, V = synth.generate(wl)
+    lse = synth.prefill_row_lse(wl, q, K)
+    assert lse.shape == (2, 4, 5)
+    off = wl.tok_off
+    for b in range(2):
+        qd, Kd = q[b].double().numpy(), K[off[b]:off[b + 1]].double().numpy()
+        a = O.attention_rows(qd, Kd, wl.n[b], wl.w, norm="prefix+window")
+        c = O.attention_rows(qd, Kd, wl.n[b], wl.w, row_lse=lse[b].double().numpy())
+        assert np.allclose(a, c, rtol=2e-5, atol=1e-12)
