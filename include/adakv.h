@@ -27,7 +27,8 @@
  *     ordinary host memory that is read during the call and may be reused on return.
  *   - The caller owns every buffer.  The library allocates nothing, frees nothing and keeps
  *     no state between calls; scratch memory comes in through `ws` (size from
- *     adakv_workspace_bytes; its contents need not survive from one call to the next).
+ *     adakv_workspace_bytes; its contents need not survive from one call to the next unless
+ *     the caller asks for that with ADAKV_FLAG_PIPELINE).
  *   - Every call only enqueues kernels on `hip_stream` (a hipStream_t, NULL = default stream)
  *     and returns; nothing synchronises with the host.  The number of output rows, sum_b B_b,
  *     is known before the call, so outputs are pre-sized by the caller.
@@ -58,6 +59,17 @@ typedef enum {
 #define ADAKV_MAX_BATCH 64          /* sequences per call                                    */
 #define ADAKV_FLAG_ROW_LSE 1u       /* bit 0 of flags: informational, set by callers that
                                        pass row_lse to adakv_score                           */
+#define ADAKV_FLAG_PIPELINE 2u      /* bit 1 of flags: a promise by the caller that adakv_score,
+                                       adakv_allocate and adakv_select are issued in this order
+                                       on one stream, for this layer, with the same ws and the
+                                       same scores buffer, and that nothing else touches ws in
+                                       between.  The library may then carry intermediate results
+                                       in ws from one call to the next (the scoring call clears
+                                       the Top-k histograms and counts the first radix digit of
+                                       every score while it still holds it), which removes four
+                                       kernel launches.  Results are identical with and without
+                                       the flag; breaking the promise gives undefined budgets and
+                                       indices (no out-of-bounds access).                      */
 
 /*
  * One attention layer's compression problem, for `batch` independent sequences (Algorithm 1

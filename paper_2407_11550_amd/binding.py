@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "lib", "libadakv.so")
 _lib = None
 
 ADAKV_BF16, ADAKV_FP32 = 0, 1
+ADAKV_FLAG_PIPELINE = 2
 MAX_BATCH = 64
 
 
@@ -217,15 +218,23 @@ def compact(layer: Layer, K, V, indices, cu_seqlens, K_out=None, V_out=None, str
     return K_out, V_out
 
 
-def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, bufs=None):
+def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, bufs=None,
+             pipeline=True):
     """The whole step: the four calls back to back on one stream, no host synchronisation.
     `bufs` may carry pre-allocated outputs (scores, budgets, cu_seqlens, indices, K_out, V_out)."""
     b = bufs or {}
     if ws is None:
         ws = torch.empty(max(workspace_bytes(layer), 16), dtype=torch.uint8, device=K.device)
-    sc = score(layer, q_window, K, row_lse=row_lse, out=b.get("scores"), ws=ws, stream=stream)
-    bud, cu = allocate(layer, sc, b.get("budgets"), b.get("cu_seqlens"), ws=ws, stream=stream)
-    idx = select(layer, sc, bud, cu, b.get("indices"), ws=ws, stream=stream)
+    # the three calls below keep the promise ADAKV_FLAG_PIPELINE asks for
+    saved = layer.c.flags
+    if pipeline:
+        layer.c.flags = saved | ADAKV_FLAG_PIPELINE
+    try:
+        sc = score(layer, q_window, K, row_lse=row_lse, out=b.get("scores"), ws=ws, stream=stream)
+        bud, cu = allocate(layer, sc, b.get("budgets"), b.get("cu_seqlens"), ws=ws, stream=stream)
+        idx = select(layer, sc, bud, cu, b.get("indices"), ws=ws, stream=stream)
+    finally:
+        layer.c.flags = saved
     K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
     return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
 

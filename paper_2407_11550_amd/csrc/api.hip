@@ -59,10 +59,16 @@ static int build_tables(const adakv_layer *L, SeqTab &st, Dims &dm) {
   return ADAKV_OK;
 }
 
+// Workspace: the scoring part first, the Top-k part behind it (they must not overlap: in
+// pipeline mode the scoring call already writes into the Top-k part).
+static size_t topk_offset(const SeqTab &st, const Dims &dm, int dtype) {
+  return align_up(plan_score(st, dm, dtype).total, 256);
+}
 static size_t workspace_for(const SeqTab &st, const Dims &dm, int dtype) {
-  size_t a = plan_score(st, dm, dtype).total;
-  size_t b = plan_topk_bytes(st, dm);
-  return (a > b ? a : b) + 256;
+  return topk_offset(st, dm, dtype) + plan_topk_bytes(st, dm) + 256;
+}
+static bool pipeline_mode(const adakv_layer *L, const Dims &dm) {
+  return (L->flags & ADAKV_FLAG_PIPELINE) != 0 && carry_supported(dm, L->dtype);
 }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -136,8 +142,10 @@ int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   ScorePlan pl = plan_score(st, dm, L->dtype);
   hipStream_t s = (hipStream_t)hip_stream;
+  TopkCarry tc = {nullptr, 0u, nullptr, nullptr};
+  if (pipeline_mode(L, dm)) tc = plan_carry(st, dm, wsp + topk_offset(st, dm, L->dtype));
   hipError_t e = mfma_path_supported(dm, L->dtype)
-                     ? launch_score_mfma(st, dm, q_window, K, row_lse, scores, wsp, pl, s)
+                     ? launch_score_mfma(st, dm, q_window, K, row_lse, scores, wsp, pl, tc, s)
                      : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
                                             pl, s);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
@@ -152,7 +160,9 @@ int adakv_allocate(const adakv_layer *L, const float *scores, int32_t *budgets,
   if (!aligned16(scores)) return ADAKV_EUNSUPPORTED;
   if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
-  hipError_t e = launch_allocate(st, dm, scores, budgets, cu_seqlens, wsp, (hipStream_t)hip_stream);
+  hipError_t e = launch_allocate(st, dm, scores, budgets, cu_seqlens,
+                                 wsp + topk_offset(st, dm, L->dtype), pipeline_mode(L, dm),
+                                 (hipStream_t)hip_stream);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
@@ -166,7 +176,8 @@ int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budge
   if (!aligned16(scores)) return ADAKV_EUNSUPPORTED;
   if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
-  hipError_t e = launch_select(st, dm, scores, budgets, cu_seqlens, indices, wsp,
+  hipError_t e = launch_select(st, dm, scores, budgets, cu_seqlens, indices,
+                               wsp + topk_offset(st, dm, L->dtype), pipeline_mode(L, dm),
                                (hipStream_t)hip_stream);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }

@@ -54,6 +54,8 @@ constexpr int RADIX_BINS = 2048;   // 11-bit digits: passes take bits 31..21, 20
 constexpr int SEL_CHUNK = 4096;    // positions per block in the histogram and emit kernels
 constexpr int GEN_CHUNK = 256;     // keys per block in the plain-FMA scoring kernels
 
+struct TopkCarry;
+
 // ---- scoring (score_generic.hip, score_mfma.hip) ------------------------------------------
 struct ScorePlan {                  // byte offsets into the workspace
   size_t part_m, part_l;            // [chunks][h_q*w] partial row max / sum of exp
@@ -70,15 +72,37 @@ hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, con
                                 const ScorePlan &pl, hipStream_t s);
 hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
                              const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-                             hipStream_t s);
+                             const TopkCarry &tc, hipStream_t s);
 
 // ---- allocation and selection (select.hip) --------------------------------------------------
+// A score becomes a 32-bit key whose unsigned order is the float order (+0.0f turns -0 into +0;
+// non-negative floats order like their bit patterns, the general transform keeps the order for
+// negative inputs too).  The first radix digit is the key's top 11 bits.
+__device__ __forceinline__ unsigned key_of(float x) {
+  const unsigned u = __float_as_uint(x + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Pipeline mode (ADAKV_FLAG_PIPELINE): the scoring call clears the Top-k histograms and files
+// the first radix digit of every score it writes, so that allocation and selection start at
+// their second pass.  Pointers into the Top-k part of the workspace; all null when off.
+struct TopkCarry {
+  unsigned *zero_begin;    // cleared before anything is counted
+  unsigned zero_words;
+  unsigned *hist0;         // u32 [batch*h][RADIX_BINS]  first-digit counts per head
+  unsigned *hist_tot0;     // u32 [batch][RADIX_BINS]    the same summed over the heads of a sequence
+};
+bool carry_supported(const Dims &dm, int dtype);
+TopkCarry plan_carry(const SeqTab &st, const Dims &dm, char *ws_topk);
+void launch_topk_clear(const TopkCarry &tc, hipStream_t s);
+
 size_t plan_topk_bytes(const SeqTab &st, const Dims &dm);
+// carried: the first-digit histograms are already in the workspace and the rest is cleared
 hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores, int *budgets,
-                           int *cu_seqlens, char *ws, hipStream_t s);
+                           int *cu_seqlens, char *ws, bool carried, hipStream_t s);
 hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
                          const int *budgets, const int *cu_seqlens, int *indices, char *ws,
-                         hipStream_t s);
+                         bool carried, hipStream_t s);
 
 // ---- compaction (compact.hip) ---------------------------------------------------------------
 hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const void *K,

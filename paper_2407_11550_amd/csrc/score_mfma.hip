@@ -54,7 +54,8 @@ template <int D, int MB, int RS, int KG, int CHUNK, int PASS>
 __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     SeqTab st, ChunkTab ct, Dims dm, float c_log2, const unsigned short *__restrict__ q,
     const unsigned short *__restrict__ K, const float *__restrict__ lse,
-    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ out, int halo) {
+    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ out, int halo,
+    TopkCarry tc) {
   constexpr int NW = RS * KG;                // wavefronts per workgroup
   constexpr int NT = 64 * NW;
   constexpr int KS = D / 16;                 // MFMA k-steps per tile
@@ -68,8 +69,19 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   constexpr int HALO = TILE;                 // keys scored on either side of the chunk for the pool
   __shared__ float sh_part[PASS == 2 ? RS : 1][PASS == 2 ? CHUNK + 2 * HALO : 1];
   __shared__ float sh_cm[PASS == 2 ? NT : 1], sh_cl[PASS == 2 ? NT : 1];
+  __shared__ unsigned sh_hist[PASS == 2 ? RADIX_BINS : 1];   // first radix digits of the chunk's scores
 
   const int tid = threadIdx.x, lane = tid & 63;
+  // Pipeline mode: the statistics sweep clears the Top-k histograms (they are first touched by
+  // the kernel after it), the weights sweep counts the first digit of every score it writes.
+  if (PASS == 1 && tc.zero_begin) {
+    for (unsigned i = blockIdx.x * NT + tid; i < tc.zero_words; i += gridDim.x * NT)
+      tc.zero_begin[i] = 0u;
+  }
+  if (PASS == 2 && tc.hist0) {
+    for (int i = tid; i < RADIX_BINS; i += NT) sh_hist[i] = 0u;
+  }
+
   // the wavefront index is the same in all lanes: telling the compiler keeps everything derived
   // from it (tile numbers, K addresses, loop conditions) in scalar registers
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -386,13 +398,27 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
       float m = sh_part[0][lo - k0];
       for (int t = lo + 1; t <= hi; ++t) m = fmaxf(m, sh_part[0][t - k0]);
       dst[key] = m;
+      if (tc.hist0) atomicAdd(&sh_hist[key_of(m) >> 21], 1u);
+    }
+    if (tc.hist0) {
+      __syncthreads();
+      unsigned *gh = tc.hist0 + (size_t)(b * h + c) * RADIX_BINS;
+      unsigned *gt = tc.hist_tot0 + (size_t)b * RADIX_BINS;
+      for (int i = tid; i < RADIX_BINS; i += NT) {
+        const unsigned v = sh_hist[i];
+        if (v) {
+          atomicAdd(&gh[i], v);
+          atomicAdd(&gt[i], v);
+        }
+      }
     }
   }
 }
 
 template <int D, int MB, int RS, int KG, int CHUNK>
 void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
-              const float *row_lse, float *scores, char *ws, const ScorePlan &pl, hipStream_t s) {
+              const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
+              const TopkCarry &tc, hipStream_t s) {
   const ChunkTab ct = make_chunks(st, CHUNK);
   const int nblk = ct.off[st.batch] * dm.h_kv;
   const float c_log2 = dm.scale * LOG2E;
@@ -411,40 +437,42 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
     ADAKV_LAUNCH("score_stats_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 1>), dim3(nblk),
                  block, s, st, ct, dm, c_log2, (const unsigned short *)q,
                  (const unsigned short *)K, (const float *)nullptr, part_m, part_l,
-                 (float *)nullptr, 0);
+                 (float *)nullptr, 0, tc);
     if (!fuse_lse) {
       launch_lse_combine(st, ct, dm.h_q * dm.w, part_m, part_l, lse, s);
       use_lse = lse;
     }
+  } else if (tc.zero_begin) {
+    launch_topk_clear(tc, s);                 // no statistics sweep to do the clearing
   }
   ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 2>), dim3(nblk),
                block, s, st, ct, dm, c_log2, (const unsigned short *)q, (const unsigned short *)K,
-               use_lse, part_m, part_l, fuse_pool ? scores : raw, fuse_pool ? 1 : 0);
+               use_lse, part_m, part_l, fuse_pool ? scores : raw, fuse_pool ? 1 : 0, tc);
   if (!fuse_pool) launch_pool(st, dm, raw, scores, s);
 }
 
 template <int D>
 void run_mfma_d(const SeqTab &st, const Dims &dm, const void *q, const void *K,
                 const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-                hipStream_t s) {
+                const TopkCarry &tc, hipStream_t s) {
   const int R = dm.g * dm.w;
-  if (R <= 32) run_mfma<D, 1, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else if (R <= 64) run_mfma<D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  if (R <= 32) run_mfma<D, 1, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  else if (R <= 64) run_mfma<D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
   else if (R <= 128) {
     // chunk length: long chunks amortise the per-workgroup set-up, but every compute unit wants
     // a few workgroups to choose from
     long long keys = 0;
     for (int b = 0; b < st.batch; ++b) keys += st.n[b];
     const long long wg2048 = (keys / 2048 + st.batch) * dm.h_kv;
-    if (wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, s);
-    else if (2 * wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
-    else run_mfma<D, 2, 2, 2, 512>(st, dm, q, K, row_lse, scores, ws, pl, s);
+    if (wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    else if (2 * wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    else run_mfma<D, 2, 2, 2, 512>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
   }
-  else if (R <= 256) run_mfma<D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else if (R <= 256) run_mfma<D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
   // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
   // a tile half the loads, so four wavefronts of 128 rows
-  else if constexpr (D == 128) run_mfma<D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else run_mfma<D, 4, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, s);
+  else if constexpr (D == 128) run_mfma<D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  else run_mfma<D, 4, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
 }
 
 }  // namespace
@@ -457,9 +485,9 @@ bool mfma_path_supported(const Dims &dm, int dtype) {
 
 hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
                              const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-                             hipStream_t s) {
-  if (dm.d == 64) run_mfma_d<64>(st, dm, q, K, row_lse, scores, ws, pl, s);
-  else run_mfma_d<128>(st, dm, q, K, row_lse, scores, ws, pl, s);
+                             const TopkCarry &tc, hipStream_t s) {
+  if (dm.d == 64) run_mfma_d<64>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  else run_mfma_d<128>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
   return hipGetLastError();
 }
 

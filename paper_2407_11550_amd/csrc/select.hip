@@ -21,10 +21,11 @@ namespace adakv {
 
 namespace {
 
-struct TopkWs {             // byte offsets inside the workspace
-  size_t hist;              // u32 [3][batch*h][RADIX_BINS]  per-head digit counts
-  size_t hist_tot;          // u32 [3][batch][RADIX_BINS]    the same summed over heads (layer scope)
-  size_t zero_end;          // everything before this is cleared by the init kernel
+struct TopkWs {             // byte offsets inside the Top-k part of the workspace
+  size_t hist;              // u32 [3][batch*h][RADIX_BINS]  per-head digit counts, layer scope
+  size_t hist_tot;          // u32 [3][batch][RADIX_BINS]    the same summed over heads
+  size_t hist_sel;          // u32 [3][batch*h][RADIX_BINS]  per-head digit counts, head scope
+  size_t zero_end;          // everything before this starts at zero
   size_t state;             // uint2 [2][batch*h]: (digits chosen, rank left) after passes 0 and 1
   size_t chunk_cnt;         // i32 [chunks][h][2]
   size_t total;
@@ -36,6 +37,7 @@ TopkWs plan(const SeqTab &st, const Dims &dm) {
   size_t o = 0;
   p.hist = o; o += 3 * nseg * RADIX_BINS * 4;
   p.hist_tot = o; o += 3 * (size_t)st.batch * RADIX_BINS * 4;
+  p.hist_sel = o; o += 3 * nseg * RADIX_BINS * 4;
   p.zero_end = o;
   p.state = o; o += align_up(2 * nseg * 8, 256);
   p.chunk_cnt = o;
@@ -44,12 +46,11 @@ TopkWs plan(const SeqTab &st, const Dims &dm) {
   return p;
 }
 
-__device__ __forceinline__ unsigned key_of(float x) {
-  // +0.0f turns -0 into +0.  Non-negative floats order like their bit patterns; the general
-  // transform keeps the order for negative inputs too.
-  unsigned u = __float_as_uint(x + 0.0f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
+// The per-head histograms of the three passes of one scope.  The first digit of a score does not
+// depend on the scope, so in pipeline mode the head scope reads the layer scope's pass-0 counts.
+struct HistSet {
+  unsigned *p[3];           // each [batch*h][RADIX_BINS]
+};
 
 template <int P> __device__ __forceinline__ bool matches(unsigned key, unsigned prefix) {
   if (P == 0) return true;
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256) void topk_init_kernel(unsigned *__restrict__ z
 template <int P, bool LAYER>
 __device__ __forceinline__ Rank rank_before_pass(const SeqTab &st, int h, int b, int c,
                                                  const int *__restrict__ budgets,
-                                                 const unsigned *__restrict__ hist,
+                                                 const HistSet &hist,
                                                  const unsigned *__restrict__ hist_tot,
                                                  const uint2 *__restrict__ state, unsigned *sh) {
   const int nsegs = st.batch * h;
@@ -157,7 +158,7 @@ __device__ __forceinline__ Rank rank_before_pass(const SeqTab &st, int h, int b,
     constexpr int Q = P - 1;                           // the pass whose histogram is scanned
     constexpr int NBQ = (Q == 2) ? 1024 : RADIX_BINS;
     const unsigned *bins = LAYER ? hist_tot + ((size_t)Q * st.batch + b) * RADIX_BINS
-                                 : hist + ((size_t)Q * nsegs + b * h + c) * RADIX_BINS;
+                                 : hist.p[Q] + (size_t)(b * h + c) * RADIX_BINS;
     // the histogram and the stored state do not depend on each other: both loads go out now
     const Bins<NBQ> mine = load_bins<NBQ>(bins);
     if (P == 1) {
@@ -183,7 +184,7 @@ template <int P, bool LAYER>
 __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, int h,
                                                         const float *__restrict__ scores,
                                                         const int *__restrict__ budgets,
-                                                        unsigned *__restrict__ hist,
+                                                        HistSet hist,
                                                         unsigned *__restrict__ hist_tot,
                                                         uint2 *__restrict__ state) {
   constexpr int NB = (P == 2) ? 1024 : RADIX_BINS;
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
     if (j0 + tid + 256 * i < j1 && matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
   }
   __syncthreads();
-  unsigned *gh = hist + ((size_t)P * nsegs + b * h + c) * RADIX_BINS;
+  unsigned *gh = hist.p[P] + (size_t)(b * h + c) * RADIX_BINS;
   unsigned *gt = hist_tot + ((size_t)P * st.batch + b) * RADIX_BINS;
   for (int i = tid; i < NB; i += 256) {
     const unsigned v = lh[i];
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
 // Layer scope, after the third pass: Algorithm 1's counts f_c and the safeguard of Alg. 2 l.8.
 // One block per sequence.
 __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int w, int alpha_fix,
-                                                           const unsigned *__restrict__ hist,
+                                                           HistSet hist,
                                                            const unsigned *__restrict__ hist_tot,
                                                            const uint2 *__restrict__ state,
                                                            int *__restrict__ budgets,
@@ -248,9 +249,9 @@ __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int
   auto load_head = [&](int c) {
     HeadBins hb;
     const int cc = min(c, h - 1);
-    const uint4 *b0 = reinterpret_cast<const uint4 *>(hist + ((size_t)0 * nsegs + b * h + cc) * RADIX_BINS) + lane * 8;
-    const uint4 *b1 = reinterpret_cast<const uint4 *>(hist + ((size_t)1 * nsegs + b * h + cc) * RADIX_BINS) + lane * 8;
-    const uint4 *b2 = reinterpret_cast<const uint4 *>(hist + ((size_t)2 * nsegs + b * h + cc) * RADIX_BINS) + lane * 4;
+    const uint4 *b0 = reinterpret_cast<const uint4 *>(hist.p[0] + (size_t)(b * h + cc) * RADIX_BINS) + lane * 8;
+    const uint4 *b1 = reinterpret_cast<const uint4 *>(hist.p[1] + (size_t)(b * h + cc) * RADIX_BINS) + lane * 8;
+    const uint4 *b2 = reinterpret_cast<const uint4 *>(hist.p[2] + (size_t)(b * h + cc) * RADIX_BINS) + lane * 4;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { hb.v0[i] = b0[i]; hb.v1[i] = b1[i]; }
 #pragma unroll
@@ -368,7 +369,7 @@ constexpr int EPT = SEL_CHUNK / 256;   // consecutive positions per thread in th
 
 // Head scope, after the third pass: (threshold key, number of threshold-valued positions to take)
 __device__ __forceinline__ Rank head_threshold(const SeqTab &st, int h, int b, int c,
-                                               const unsigned *__restrict__ hist,
+                                               const HistSet &hist,
                                                const uint2 *__restrict__ state, unsigned *sh) {
   Rank r = rank_before_pass<3, false>(st, h, b, c, nullptr, hist, nullptr, state, sh);
   if (r.krem <= 0) { r.prefix = 0xFFFFFFFFu; r.krem = 0; }   // no key is above, no tie is taken
@@ -377,7 +378,7 @@ __device__ __forceinline__ Rank head_threshold(const SeqTab &st, int h, int b, i
 
 __global__ __launch_bounds__(256) void emit_count_kernel(SeqTab st, ChunkTab ct, int h,
                                                          const float *__restrict__ scores,
-                                                         const unsigned *__restrict__ hist,
+                                                         HistSet hist,
                                                          const uint2 *__restrict__ state,
                                                          int *__restrict__ chunk_cnt) {
   __shared__ unsigned sh[8];
@@ -408,7 +409,7 @@ __global__ __launch_bounds__(256) void emit_count_kernel(SeqTab st, ChunkTab ct,
 
 __global__ __launch_bounds__(256) void emit_write_kernel(
     SeqTab st, ChunkTab ct, int h, int w, const float *__restrict__ scores,
-    const unsigned *__restrict__ hist, const uint2 *__restrict__ state,
+    HistSet hist, const uint2 *__restrict__ state,
     const int *__restrict__ chunk_cnt, const int *__restrict__ budgets,
     const int *__restrict__ cu, int *__restrict__ indices, int rows_total) {
   __shared__ unsigned sh[8];
@@ -460,14 +461,14 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
     if (j >= n) break;
     const bool isg = keys[i] > thr, ise = keys[i] == thr;
     const int pos = out0 + ng + min(ne, ties);
-    if ((isg || (ise && ne < ties)) && pos < rows_total) indices[pos] = j;
+    if ((isg || (ise && ne < ties)) && (unsigned)pos < (unsigned)rows_total) indices[pos] = j;
     ng += isg;
     ne += ise;
   }
   if (chunk == 0) {
     const int bud = budgets[seg];
     for (int rr = tid; rr < w; rr += 256)
-      if (out0 + bud + rr < rows_total) indices[out0 + bud + rr] = n + rr;
+      if ((unsigned)(out0 + bud + rr) < (unsigned)rows_total) indices[out0 + bud + rr] = n + rr;
   }
 }
 
@@ -475,37 +476,73 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
 
 size_t plan_topk_bytes(const SeqTab &st, const Dims &dm) { return plan(st, dm).total; }
 
+// Pipeline mode needs a scoring kernel that files the first digits itself: the MFMA path with the
+// max-pool fused into it.
+bool carry_supported(const Dims &dm, int dtype) {
+  return mfma_path_supported(dm, dtype) && dm.pool_k / 2 <= 32;
+}
+
+TopkCarry plan_carry(const SeqTab &st, const Dims &dm, char *ws_topk) {
+  const TopkWs p = plan(st, dm);
+  TopkCarry tc;
+  tc.zero_begin = (unsigned *)ws_topk;
+  tc.zero_words = (unsigned)(p.zero_end / 4);
+  tc.hist0 = (unsigned *)(ws_topk + p.hist);
+  tc.hist_tot0 = (unsigned *)(ws_topk + p.hist_tot);
+  return tc;
+}
+
+static void launch_clear(const char *name, unsigned *begin, size_t words, hipStream_t s) {
+  int zb = (int)((words + 256 * 4 - 1) / (256 * 4));
+  if (zb < 1) zb = 1;
+  if (zb > 1024) zb = 1024;
+  ADAKV_LAUNCH(name, topk_init_kernel, dim3(zb), dim3(256), s, begin, words);
+}
+
+void launch_topk_clear(const TopkCarry &tc, hipStream_t s) {
+  launch_clear("score_hist_clear", tc.zero_begin, tc.zero_words, s);
+}
+
+static HistSet hist_set(char *ws, const TopkWs &p, const SeqTab &st, const Dims &dm, bool layer,
+                        bool carried) {
+  const size_t per_pass = (size_t)st.batch * dm.h_kv * RADIX_BINS;
+  unsigned *own = (unsigned *)(ws + (layer ? p.hist : p.hist_sel));
+  HistSet hs;
+  for (int q = 0; q < 3; ++q) hs.p[q] = own + q * per_pass;
+  if (!layer && carried) hs.p[0] = (unsigned *)(ws + p.hist);   // first digits: scope-independent
+  return hs;
+}
+
 template <bool LAYER>
 static void run_passes(const SeqTab &st, const Dims &dm, const float *scores,
                        const int *budgets_in, const TopkWs &p, const ChunkTab &ct, char *ws,
-                       hipStream_t s) {
+                       bool carried, hipStream_t s) {
   const int h = dm.h_kv;
-  unsigned *hist = (unsigned *)(ws + p.hist);
+  const HistSet hist = hist_set(ws, p, st, dm, LAYER, carried);
   unsigned *hist_tot = (unsigned *)(ws + p.hist_tot);
   uint2 *state = (uint2 *)(ws + p.state);
-  const size_t zero_words = p.zero_end / 4;
-  int zb = (int)((zero_words + 256 * 4 - 1) / (256 * 4));
-  if (zb < 1) zb = 1;
-  if (zb > 1024) zb = 1024;
-  ADAKV_LAUNCH(LAYER ? "alloc_init" : "select_init", topk_init_kernel, dim3(zb), dim3(256), s,
-               (unsigned *)ws, zero_words);
   dim3 grid(ct.off[st.batch], h), block(256);
 #define ADAKV_PASS(P)                                                                          \
   ADAKV_LAUNCH(LAYER ? "alloc_pass" #P : "select_pass" #P, (topk_hist_kernel<P, LAYER>), grid,   \
                block, s, st, ct, h, scores, budgets_in, hist, hist_tot, state)
-  ADAKV_PASS(0);
+  if (!carried) {
+    // this scope's own histograms (the layer scope's include the per-sequence totals)
+    if (LAYER) launch_clear("alloc_init", (unsigned *)(ws + p.hist), (p.hist_sel - p.hist) / 4, s);
+    else launch_clear("select_init", (unsigned *)(ws + p.hist_sel), (p.zero_end - p.hist_sel) / 4, s);
+    ADAKV_PASS(0);
+  }
   ADAKV_PASS(1);
   ADAKV_PASS(2);
 #undef ADAKV_PASS
 }
 
 hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores, int *budgets,
-                           int *cu_seqlens, char *ws, hipStream_t s) {
+                           int *cu_seqlens, char *ws, bool carried, hipStream_t s) {
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
-  run_passes<true>(st, dm, scores, nullptr, p, ct, ws, s);
+  run_passes<true>(st, dm, scores, nullptr, p, ct, ws, carried, s);
   ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(256), s, st, dm.h_kv,
-               dm.w, dm.alpha_fix, (const unsigned *)(ws + p.hist),
+               dm.w, dm.alpha_fix, hist_set(ws, p, st, dm, true, carried),
                (const unsigned *)(ws + p.hist_tot), (const uint2 *)(ws + p.state), budgets,
                cu_seqlens);
   return hipGetLastError();
@@ -513,18 +550,17 @@ hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores
 
 hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
                          const int *budgets, const int *cu_seqlens, int *indices, char *ws,
-                         hipStream_t s) {
+                         bool carried, hipStream_t s) {
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
-  run_passes<false>(st, dm, scores, budgets, p, ct, ws, s);
+  run_passes<false>(st, dm, scores, budgets, p, ct, ws, carried, s);
+  const HistSet hist = hist_set(ws, p, st, dm, false, carried);
   dim3 grid(ct.off[st.batch], dm.h_kv), block(256);
-  ADAKV_LAUNCH("select_count", emit_count_kernel, grid, block, s, st, ct, dm.h_kv, scores,
-               (const unsigned *)(ws + p.hist), (const uint2 *)(ws + p.state),
-               (int *)(ws + p.chunk_cnt));
+  ADAKV_LAUNCH("select_count", emit_count_kernel, grid, block, s, st, ct, dm.h_kv, scores, hist,
+               (const uint2 *)(ws + p.state), (int *)(ws + p.chunk_cnt));
   ADAKV_LAUNCH("select_emit", emit_write_kernel, grid, block, s, st, ct, dm.h_kv, dm.w, scores,
-               (const unsigned *)(ws + p.hist), (const uint2 *)(ws + p.state),
-               (const int *)(ws + p.chunk_cnt), budgets, cu_seqlens, indices,
-               st.out_off[st.batch]);
+               hist, (const uint2 *)(ws + p.state), (const int *)(ws + p.chunk_cnt), budgets,
+               cu_seqlens, indices, st.out_off[st.batch]);
   return hipGetLastError();
 }
 

@@ -255,7 +255,7 @@ def test_kernel_trace_names_every_kernel_and_costs_nothing_when_disarmed():
     torch.cuda.synchronize()
     names = [n for n, _ in tr.durations_us()]
     assert names[0].startswith("score_") and names[-1] == "compact"
-    assert sum(n.startswith("alloc_") for n in names) >= 4 and sum(n.startswith("select_") for n in names) >= 5
+    assert sum(n.startswith("alloc_") for n in names) >= 3 and sum(n.startswith("select_") for n in names) >= 4
     assert all(0 < us < 1e5 for _, us in tr.durations_us()) and tr.used == 2 * len(names)
     for key in ref:
         assert torch.equal(ref[key], out[key]), key
@@ -270,3 +270,33 @@ def test_sixty_four_sequences_in_one_call():
     q, K, V = synth.generate(wl, device=DEV)
     _, out = _run(wl, q, K, V)
     _check_all(wl, q, K, V, out)
+
+
+@pytest.mark.parametrize("case", [
+    (32, 8, 128, 32, 7, [4099], [8 * 250], None),              # two sweeps clear and count
+    (32, 8, 128, 32, 7, [9000, 700, 2048], [8 * 300, 8 * 40, 8 * 2080], None),   # ragged, one full budget
+    (8, 2, 128, 32, 7, [3000], [2 * 300], "lse"),              # row_lse given: clearing kernel instead
+    (16, 2, 128, 64, 7, [2500], [2 * 400], None),              # 512 window rows per head
+    (4, 4, 64, 8, 7, [1024], [4 * 128], None),                 # fp32: the flag is accepted and ignored
+], ids=["one_seq", "ragged", "row_lse", "rows512", "fp32"])
+def test_pipeline_flag_changes_nothing(case):
+    """ADAKV_FLAG_PIPELINE (scoring clears the histograms and counts first digits itself) must
+    give bit-identical scores, budgets, offsets, indices and rows."""
+    h_q, h, d, w, k, n, B, mode = case
+    _say(f"pipeline flag {case}")
+    dt = torch.float32 if d == 64 else torch.bfloat16
+    wl = synth.small_workload(h_q, h, d, w, k, n, B, dtype=dt, seed=23)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl)
+    lse = synth.prefill_row_lse(wl, q, K) if mode == "lse" else None
+    ws = torch.empty(adakv.workspace_bytes(layer), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xAB)                                           # stale bytes in the workspace
+    a = adakv.compress(layer, q, K, V, row_lse=lse, ws=ws, pipeline=False)
+    ws.fill_(0xCD)
+    b = adakv.compress(layer, q, K, V, row_lse=lse, ws=ws, pipeline=True)
+    c = adakv.compress(layer, q, K, V, row_lse=lse, ws=ws, pipeline=True)      # on its own leftovers
+    torch.cuda.synchronize()
+    for key in a:
+        assert torch.equal(a[key], b[key]), key
+        assert torch.equal(a[key], c[key]), key
+    assert int(a["budgets"].sum()) == sum(B) - w * h * len(n)
