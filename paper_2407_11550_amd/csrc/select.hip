@@ -229,8 +229,8 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
 }
 
 // Layer scope, after the third pass: Algorithm 1's counts f_c and the safeguard of Alg. 2 l.8.
-// One block per sequence.
-__global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int w, int alpha_fix,
+// One block of eight wavefronts per sequence.
+__global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, int h, int w, int alpha_fix,
                                                            HistSet hist,
                                                            const unsigned *__restrict__ hist_tot,
                                                            const uint2 *__restrict__ state,
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int
   const int b = blockIdx.x;
   const int nsegs = st.batch * h;
   if (tid < 64) { sh_gt[tid] = 0; sh_eq[tid] = 0; }
-  // Wavefront wv takes heads wv, wv+4, ...; a lane loads all its bins of the three histograms
+  // Wavefront wv takes heads wv, wv+8, ...; a lane loads all its bins of the three histograms
   // of a head at once (20 independent 16-byte loads).  The first head's loads are issued before
   // the threshold is known (they do not depend on it), so they share its round trip.
   struct HeadBins { uint4 v0[8], v1[8], v2[4]; };
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(256) void alloc_finish_kernel(SeqTab st, int h, int
   // those in higher bins of pass 0, plus higher bins of pass 1 under the same first digit, ...
   if (r.krem > 0) {
     const unsigned d0 = digit_of<0>(r.prefix), d1 = digit_of<1>(r.prefix), d2 = digit_of<2>(r.prefix);
-    for (int c = wv; c < h; c += 4) {
+    for (int c = wv; c < h; c += 8) {
       const HeadBins hb = (c == wv) ? first : load_head(c);
       int cnt = 0, eq = 0;
 #pragma unroll
@@ -541,7 +541,7 @@ hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
   run_passes<true>(st, dm, scores, nullptr, p, ct, ws, carried, s);
-  ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(256), s, st, dm.h_kv,
+  ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(512), s, st, dm.h_kv,
                dm.w, dm.alpha_fix, hist_set(ws, p, st, dm, true, carried),
                (const unsigned *)(ws + p.hist_tot), (const uint2 *)(ws + p.state), budgets,
                cu_seqlens);
