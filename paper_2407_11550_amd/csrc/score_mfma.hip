@@ -97,9 +97,13 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   const int R = dm.g * dm.w, RQ = dm.h_q * dm.w;
   const int kc0 = chunk * CHUNK;             // first key of the chunk
   const int kc1 = min(n, kc0 + CHUNK);
-  // sweep 2 with the pool fused also scores one tile of neighbours on each side
+  // sweep 2 with the pool fused also scores the neighbours the pool looks at: a whole tile in
+  // front of the chunk (tiles stay aligned), the pool radius behind it.  No tile may start past
+  // the last key somebody needs: the row clamp in load_set counts rows from the tile set's
+  // first key and must never go below it.
+  const int pool_r = (PASS == 2 && halo) ? dm.pool_k / 2 : 0;
   const int k0 = (PASS == 2 && halo && kc0 > 0) ? kc0 - HALO : kc0;
-  const int k1 = (PASS == 2 && halo) ? min(n, kc1 + HALO) : kc1;
+  const int k1 = (PASS == 2 && halo) ? min(n, kc1 + pool_r) : kc1;
   const int ntiles = (k1 - k0 + TILE - 1) / TILE;
   const int row0 = rs * RW;                  // first window row of this wavefront
   const size_t head_row0 = (size_t)b * RQ + (size_t)c * R;
@@ -144,11 +148,12 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // halo tiles only the pool radius next to the chunk is fetched, the other rows repeat the
   // nearest needed one (a cache hit) and their results are never looked at.
   // tok_bytes < 2^24 is checked on the host.
-  const int pool_r = (PASS == 2 && halo) ? dm.pool_k / 2 : 0;
   const int need_lo = max(kc0 - pool_r, 0), need_hi = min(kc1 - 1 + pool_r, n - 1);
   auto load_set = [&](u32x4 (&g)[LDPT], int it) {
     const int key0 = k0 + it * KG * TILE;              // first key of the iteration
-    const int lim = need_hi - key0, lo = need_lo - key0;
+    // both bounds are kept at or above zero, so the clamped row is never negative (it goes
+    // through an unsigned 24-bit multiply); key0 <= need_hi holds by the choice of k1 above
+    const int lim = max(need_hi - key0, 0), lo = max(need_lo - key0, 0);
     const char *sb = kbase + (size_t)key0 * tok_bytes;
 #pragma unroll
     for (int i = 0; i < LDPT; ++i) {

@@ -249,3 +249,51 @@ def test_decode_rejects_bad_arguments():
     with pytest.raises(adakv.AdaKVError) as e:
         adakv.decode_attn(layer2, q[0], cu, -1, Kc, Vc, seg_len, ws=torch.empty(1 << 20, dtype=torch.uint8, device=DEV))
     assert e.value.status == -1
+
+
+def test_eviction_loss_adaptive_against_uniform_allocation():
+    """Both halves together, on the quantity the paper optimises (Section 3.2, Eqs. 4-5): the L1
+    distance between the layer output with the full cache and with the compressed cache, for
+    one decoding query right after prefill.  alpha = 1 is the uniform allocation, alpha = 0
+    Algorithm 1 alone.  With one observation row (w = 1), no pooling and the decoding query equal
+    to that row, the scores are exactly the attention weights of the query, so alpha = 0 retains
+    the largest possible weight (Theorem 3.3) and its loss bound is the smallest; the measured
+    loss follows it on these layers (a few heads concentrated, the others dispersed).
+    The output projection is left out (W^O = identity per head), which the bound allows."""
+    _say("eviction loss")
+    losses = {0.0: [], 0.2: [], 1.0: []}
+    kept = {0.0: [], 0.2: [], 1.0: []}
+    for seed in range(6):
+        n = 6000
+        for alpha in losses:
+            wl = synth.small_workload(8, 8, 128, 1, 1, [n], [8 * (1 + 150)], alpha=alpha, seed=100 + seed,
+                                      temps=(0.5, 6.0), planted=(4, 400))
+            q, K, V = synth.generate(wl, device=DEV)
+            layer = adakv.Layer.from_workload(wl)
+            res = adakv.compress(layer, q, K, V)
+            Kc, Vc, seg_len = adakv.cache_build(layer, K, V, res["indices"], res["cu_seqlens"], 0)
+            qn = q[:, :, 0, :].contiguous()                       # the window row itself decodes
+            out_c = adakv.decode_attn(layer, qn, res["cu_seqlens"], 0, Kc, Vc, seg_len)
+            # the full cache is a compressed cache with nothing evicted
+            wl_full = synth.small_workload(8, 8, 128, 1, 1, [n], [8 * (1 + n)], alpha=alpha, seed=100 + seed,
+                                           temps=(0.5, 6.0), planted=(4, 400))
+            lf = adakv.Layer.from_workload(wl_full)
+            rf = adakv.compress(lf, q, K, V)
+            Kf, Vf, sf = adakv.cache_build(lf, K, V, rf["indices"], rf["cu_seqlens"], 0)
+            out_f = adakv.decode_attn(lf, qn, rf["cu_seqlens"], 0, Kf, Vf, sf)
+            torch.cuda.synchronize()
+            losses[alpha].append(float((out_f - out_c).abs().sum()))
+            sc = res["scores"].view(8, n)
+            idx, cu = res["indices"].long(), res["cu_seqlens"].long()
+            tot = 0.0
+            for c in range(8):
+                seg = idx[cu[c]:cu[c + 1] - 1]                    # without the window row
+                tot += float(sc[c, seg].double().sum())
+            kept[alpha].append(tot)
+    for s_ in range(6):
+        assert kept[0.0][s_] >= kept[0.2][s_] - 1e-6 and kept[0.0][s_] >= kept[1.0][s_] - 1e-6   # Theorem 3.3
+    mean = {a: float(np.mean(v)) for a, v in losses.items()}
+    _say(f"  mean L1 eviction loss: alpha 0 {mean[0.0]:.3f}, alpha 0.2 {mean[0.2]:.3f}, uniform {mean[1.0]:.3f}; "
+         f"retained weight {np.mean(kept[0.0]):.3f} / {np.mean(kept[0.2]):.3f} / {np.mean(kept[1.0]):.3f}")
+    assert mean[0.0] < mean[1.0] and mean[0.2] < mean[1.0]
+    assert sum(a < u for a, u in zip(losses[0.2], losses[1.0])) >= 5      # on most samples

@@ -50,6 +50,10 @@ SHAPES = [
     (6, 2, 128, 8, 3, 513, 64, torch.float32),        # g = 3: rows not a multiple of 16
     (4, 2, 64, 4, 1, 300, 50, torch.bfloat16),        # no pooling
     (2, 1, 128, 1, 7, 5, 3, torch.bfloat16),          # n smaller than the pool kernel
+    (8, 8, 128, 1, 1, 6000, 151, torch.bfloat16),     # no pooling over several chunks, one window row
+    (4, 2, 64, 4, 1, 5000, 90, torch.bfloat16),       # the same with d = 64
+    (4, 4, 64, 8, 1, 3000, 100, torch.float32),       # no pooling on the fp32 path
+    (8, 2, 128, 16, 3, 4500, 200, torch.bfloat16),    # pool radius 1 over several chunks
 ]
 
 
@@ -278,7 +282,8 @@ def test_sixty_four_sequences_in_one_call():
     (8, 2, 128, 32, 7, [3000], [2 * 300], "lse"),              # row_lse given: clearing kernel instead
     (16, 2, 128, 64, 7, [2500], [2 * 400], None),              # 512 window rows per head
     (4, 4, 64, 8, 7, [1024], [4 * 128], None),                 # fp32: the flag is accepted and ignored
-], ids=["one_seq", "ragged", "row_lse", "rows512", "fp32"])
+    (8, 2, 128, 32, 7, [1500, 900], [2 * 32, 2 * 33], None),   # nothing / one position to select
+], ids=["one_seq", "ragged", "row_lse", "rows512", "fp32", "empty_budget"])
 def test_pipeline_flag_changes_nothing(case):
     """ADAKV_FLAG_PIPELINE (scoring clears the histograms and counts first digits itself) must
     give bit-identical scores, budgets, offsets, indices and rows."""
