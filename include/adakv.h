@@ -252,6 +252,21 @@ int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new
                       float *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Layer budgets for the pyramidal variant (Section 3.4: Ada-Pyramid differs from Ada-SnapKV only
+ * in how the total budget is spread over the layers, "via pre-set hyper-parameters" that the
+ * paper does not give; inside a layer the algorithm is the same).  Host arithmetic only.  The
+ * schedule chosen here is linear in depth, largest at layer 0:
+ *     real_l = B_max - (B_max - B_min) * l / (n_layers - 1),  B_max = ratio * B_min,
+ *     B_min = 2 * avg_budget / (1 + ratio),  so that the mean over the layers is avg_budget;
+ * out[l] = floor(real_l) and the units still missing from n_layers * avg_budget go one each to
+ * the first layers.  ratio = 1 gives avg_budget everywhere.
+ *
+ *   out (host) [n_layers] int64, written; sum = n_layers * avg_budget, non-increasing
+ * Returns ADAKV_EINVAL for n_layers < 1, avg_budget < 0, ratio < 1 or not finite, out == NULL.
+ */
+int adakv_pyramid_budgets(int32_t n_layers, int64_t avg_budget, double ratio, int64_t *out);
+
+/*
  * Profiling aid for benchmarks (no part of the method).  While armed, on the arming host thread,
  * every kernel the library launches carries two of the caller's events, taken from the array in
  * order: events 2i and 2i+1 receive the start and the end timestamp of the i-th kernel itself

@@ -310,3 +310,24 @@ def eviction_loss_and_bound(q, K, V, WO, keep):
         C = max(C, float(np.abs(VW).sum(axis=1).max()))
         kept_mass += float(A[keep[i]].sum())
     return float(np.abs(y - y_hat).sum()), 2 * h * C - 2 * C * kept_mass
+
+
+# --------------------------------------------------------------------------- #
+# Layer budgets of the pyramidal variant (Section 3.4).  The paper leaves the schedule's
+# hyper-parameters open; reading R9: linear in depth, largest first, mean = avg, the
+# first-to-last ratio given.  Exact rational arithmetic.  Parity unpinned (the choice
+# of schedule); the properties below it are pinned in the tests.
+# --------------------------------------------------------------------------- #
+def pyramid_budgets(n_layers: int, avg_budget: int, ratio) -> list:
+    from fractions import Fraction
+    r = Fraction(ratio)
+    if n_layers == 1:
+        return [avg_budget]
+    b_min = Fraction(2 * avg_budget) / (1 + r)
+    b_max = r * b_min
+    real = [b_max - (b_max - b_min) * Fraction(l, n_layers - 1) for l in range(n_layers)]
+    out = [math.floor(x) for x in real]
+    left = n_layers * avg_budget - sum(out)
+    for l in range(left):
+        out[l % n_layers] += 1
+    return out

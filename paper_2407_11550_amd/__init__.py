@@ -7,4 +7,4 @@ and raises if the library has not been built.
 """
 from .binding import (AdaKVError, KernelTrace, Layer, allocate, append, cache_build, cache_rows,  # noqa: F401
                       compact, compress, decode_attn, decode_step, decode_workspace_bytes, library_path,
-                      load_library, score, select, workspace_bytes)
+                      load_library, pyramid_budgets, score, select, workspace_bytes)

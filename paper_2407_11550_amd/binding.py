@@ -76,6 +76,9 @@ def load_library():
         fn.argtypes = args
     lib.adakv_decode_workspace_bytes.restype = Z
     lib.adakv_decode_workspace_bytes.argtypes = [P, I]
+    lib.adakv_pyramid_budgets.restype = ctypes.c_int
+    lib.adakv_pyramid_budgets.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_double,
+                                          ctypes.POINTER(ctypes.c_int64)]
     lib.adakv_trace_arm.restype = ctypes.c_int
     lib.adakv_trace_arm.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
     lib.adakv_trace_disarm.restype = ctypes.c_int
@@ -237,6 +240,15 @@ def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, b
         layer.c.flags = saved
     K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
     return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
+
+
+def pyramid_budgets(n_layers: int, avg_budget: int, ratio: float):
+    """adakv_pyramid_budgets: per-layer budgets of the pyramidal variant, largest first."""
+    out = (ctypes.c_int64 * max(int(n_layers), 1))()
+    st = load_library().adakv_pyramid_budgets(int(n_layers), int(avg_budget), float(ratio), out)
+    if st != 0:
+        raise AdaKVError(st, "adakv_pyramid_budgets")
+    return [int(v) for v in out]
 
 
 # ---- decode side of the flattened layout ---------------------------------------------------------

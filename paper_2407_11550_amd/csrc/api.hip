@@ -101,6 +101,30 @@ size_t adakv_workspace_bytes(const adakv_layer *L) {
   return workspace_for(st, dm, L->dtype);
 }
 
+int adakv_pyramid_budgets(int32_t n_layers, int64_t avg_budget, double ratio, int64_t *out) {
+  if (n_layers < 1 || avg_budget < 0 || !(ratio >= 1.0) || isinf(ratio) || !out) return ADAKV_EINVAL;
+  if (avg_budget > (1ll << 40)) return ADAKV_EUNSUPPORTED;       // keeps every product exact in a double
+  const double b_min = 2.0 * (double)avg_budget / (1.0 + ratio);
+  const double b_max = ratio * b_min;
+  int64_t given = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    double real = (double)avg_budget;
+    if (n_layers > 1) real = b_max - (b_max - b_min) * ((double)l / (double)(n_layers - 1));
+    int64_t v = (int64_t)floor(real);
+    if (v < 0) v = 0;
+    if (v > 2 * avg_budget) v = 2 * avg_budget;
+    out[l] = v;
+    given += v;
+  }
+  // the real values average to avg_budget, so flooring leaves at most n_layers units to hand out
+  // (rounding in the last place may make it one round more or less; the loop copes with both)
+  int64_t left = (int64_t)n_layers * avg_budget - given;
+  for (int32_t l = 0; left > 0; l = (l + 1) % n_layers, --left) out[l] += 1;
+  for (int32_t l = n_layers - 1; left < 0 && l >= 0; --l)
+    if (out[l] > 0) { out[l] -= 1; ++left; }
+  return ADAKV_OK;
+}
+
 int adakv_trace_arm(void *const *events, int n_events) {
   if (!events || n_events < 2 || n_events > ADAKV_TRACE_MAX) return ADAKV_EINVAL;
   g_trace.events = events;

@@ -373,3 +373,28 @@ def test_tiny_layer_regression_vector():
     for a, b in zip(got["score_probe_hex"], want["score_probe_hex"]):
         for x, y in zip(a, b):
             assert float.fromhex(x) == pytest.approx(float.fromhex(y), rel=1e-6)
+
+
+# ---- layer budgets of the pyramidal variant (reading R9) ------------------------------------
+def test_pyramid_budgets_sum_monotone_ratio_and_uniform_case():
+    for L, avg, ratio in [(32, 1024, 4), (32, 1000, 2.5), (7, 333, 10), (1, 50, 3), (2, 5, 9), (80, 128 * 8, 1)]:
+        b = O.pyramid_budgets(L, avg, ratio)
+        assert len(b) == L and sum(b) == L * avg
+        assert all(b[i] >= b[i + 1] for i in range(L - 1)) and min(b) >= 0
+        if ratio == 1:
+            assert b == [avg] * L
+        if L > 1 and avg >= 100:
+            assert abs(b[0] / b[-1] - ratio) < 0.05 * ratio       # endpoints keep the asked ratio
+            steps = [b[i] - b[i + 1] for i in range(L - 1)]
+            assert max(steps) - min(steps) <= 2                   # linear up to rounding
+    assert O.pyramid_budgets(4, 10, 3) == [16, 11, 8, 5]          # 15, 11.67, 8.33, 5: floors sum to 39, one unit to layer 0
+
+
+def test_pyramid_budgets_c_abi_matches_oracle():
+    import paper_2407_11550_amd as adakv
+    for L, avg, ratio in [(32, 1024, 4.0), (32, 1000, 2.5), (7, 333, 10.0), (1, 50, 3.0), (2, 5, 9.0),
+                          (80, 1024, 1.0), (64, 16384, 20.0), (3, 0, 2.0), (5, 7, 1.5)]:
+        assert adakv.pyramid_budgets(L, avg, ratio) == O.pyramid_budgets(L, avg, ratio), (L, avg, ratio)
+    for bad in [(0, 10, 2.0), (4, -1, 2.0), (4, 10, 0.5), (4, 10, float("inf")), (4, 10, float("nan"))]:
+        with pytest.raises(adakv.AdaKVError):
+            adakv.pyramid_budgets(*bad)
