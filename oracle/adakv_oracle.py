@@ -314,7 +314,7 @@ def eviction_loss_and_bound(q, K, V, WO, keep):
 
 # --------------------------------------------------------------------------- #
 # Layer budgets of the pyramidal variant (Section 3.4).  The paper leaves the schedule's
-# hyper-parameters open; reading R9: linear in depth, largest first, mean = avg, the
+# hyper-parameters open; reading taken: linear in depth, largest first, mean = avg, the
 # first-to-last ratio given.  Exact rational arithmetic.  Parity unpinned (the choice
 # of schedule); the properties below it are pinned in the tests.
 # --------------------------------------------------------------------------- #
