@@ -451,9 +451,10 @@ DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom) {
   DecodePlan pl;
   const long long nseg = (long long)st.batch * dm.h_kv;
   const long long cap = (long long)st.out_off[st.batch] + nseg * headroom;
-  // rows per workgroup: as long as possible while about a thousand workgroups remain
+  // rows per workgroup: as long as possible while at least 512 workgroups remain (three fit on a
+  // compute unit, so that is most of one resident round; measured best for 50 MB to 1 GB caches)
 #ifndef ADAKV_DECODE_TARGET_WGS
-#define ADAKV_DECODE_TARGET_WGS 1024
+#define ADAKV_DECODE_TARGET_WGS 512
 #endif
 #ifndef ADAKV_DECODE_MAX_SPLIT
 #define ADAKV_DECODE_MAX_SPLIT 1024
