@@ -451,16 +451,16 @@ DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom) {
   DecodePlan pl;
   const long long nseg = (long long)st.batch * dm.h_kv;
   const long long cap = (long long)st.out_off[st.batch] + nseg * headroom;
-  // rows per workgroup: as long as possible while at least 512 workgroups remain (three fit on a
-  // compute unit, so that is most of one resident round; measured best for 50 MB to 1 GB caches)
-#ifndef ADAKV_DECODE_TARGET_WGS
-#define ADAKV_DECODE_TARGET_WGS 512
+  // Rows per workgroup.  Three workgroups fit on a compute unit, 768 on the chip: the split is
+  // the multiple of 64 rows (one load round of a workgroup) that fills one such resident round,
+  // so that all workgroups start together and none is left for a thin second round.
+#ifndef ADAKV_DECODE_ROUND_WGS
+#define ADAKV_DECODE_ROUND_WGS 752
 #endif
-#ifndef ADAKV_DECODE_MAX_SPLIT
-#define ADAKV_DECODE_MAX_SPLIT 1024
-#endif
-  int split = ADAKV_DECODE_MAX_SPLIT;
-  while (split > 64 && cap / split < ADAKV_DECODE_TARGET_WGS) split >>= 1;
+  const long long room = ADAKV_DECODE_ROUND_WGS - nseg;      // the segments' last, partial splits
+  long long want = room > 64 ? (cap + room - 1) / room : cap / 512;
+  if (want < 64) want = 64;
+  const int split = (int)((want + 63) / 64 * 64);
   pl.split = split;
   pl.nblk = (int)(cap / split + nseg);          // >= sum over segments of ceil(len / split)
   pl.part_acc = 0;
