@@ -30,9 +30,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0      # MI355X published peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # (workload, kernel) -> fetched + written bytes per launch, see profiles/llama8b_128k_hbm_traffic.md
+# and profiles/decode_llama8b_ragged_hbm_traffic.md
 MEASURED_TRAFFIC_BYTES = {
-    ("llama8b_128k", "score_stats_mfma"): int((256.43 + 0.50) * 2 ** 20),
-    ("llama8b_128k", "score_weights_mfma"): int((257.22 + 4.00) * 2 ** 20),
+    ("llama8b_128k", "score_stats_mfma"): int((256.41 + 0.90) * 2 ** 20),
+    ("llama8b_128k", "score_weights_mfma"): int((256.93 + 4.11) * 2 ** 20),
+    ("llama8b_ragged/decode", "decode_attn"): int((44.86 + 1.03) * 2 ** 20),
 }
 
 
@@ -46,6 +48,17 @@ def algorithmic_bytes(wl, kept_rows):
     gather = kept_rows * wl.d * esz * 2 * 2
     return {"score": k_stream + sc, "allocate": sc, "select": sc + kept_rows * 4,
             "compact": gather + kept_rows * 4, "k_stream": k_stream}
+
+
+def calibrate_copy(torch, dev):
+    """Three 1 GiB device-to-device copies: a known number of bytes for scaling rocprofv3's
+    FETCH_SIZE / WRITE_SIZE counters."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
 
 
 def bench_decode(args):
@@ -79,6 +92,8 @@ def bench_decode(args):
     ws = torch.empty(adakv.decode_workspace_bytes(layer, hr), dtype=torch.uint8, device=dev)
     out = torch.empty((wl.batch, wl.h_q, wl.d), dtype=torch.float32, device=dev)
     overflow = torch.zeros(1, dtype=torch.int32, device=dev)
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev)
 
     def step(i):
         Kc, Vc, cu, seg_len = sets[i % len(sets)]
@@ -114,7 +129,9 @@ def bench_decode(args):
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_attn", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes": int(dom_bytes), "avg_us": round(dom_us, 2)}
+                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name + "/decode", "decode_attn"))
+                if args.budget_frac is None else None,
+                "algorithmic_bytes": int(dom_bytes), "avg_us": round(dom_us, 2)}
     cpu = None
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
@@ -197,12 +214,7 @@ def main():
                 V_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev))
 
     if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch, dev)
 
     def step(i):
         q, K, V = sets[i % len(sets)]
