@@ -1,0 +1,45 @@
+"""A CPU model of the index arithmetic that decides which K rows the scoring kernel's lanes ask
+for (chunks, halo, tile sets, the row clamp).  The kernel turns the clamped row, counted from
+the tile set's first key, into a byte offset with an unsigned multiply, so the model checks, for
+every chunk length, tile-set size, pool radius and ragged length the launcher can choose:
+  * the clamped row is never negative and lies inside the sequence,
+  * every row somebody needs (the chunk plus the pool radius on both sides) is read unclamped,
+  * no tile set starts past the last needed key.
+The formulas are retyped from csrc/score_mfma.hip (k0, k1, need_lo, need_hi, lim, lo); the test
+documents the invariant and guards the arithmetic, it does not run the kernel."""
+import pytest
+
+TILE = 32
+HALO = 32
+
+
+def violations(n, chunk_len, kg, pool_r, halo, sweep):
+    bad = 0
+    for chunk in range((n + chunk_len - 1) // chunk_len):
+        kc0 = chunk * chunk_len
+        kc1 = min(n, kc0 + chunk_len)
+        fused = sweep == 2 and halo
+        pr = pool_r if fused else 0
+        k0 = kc0 - HALO if (fused and kc0 > 0) else kc0
+        k1 = min(n, kc1 + pr) if fused else kc1
+        ntiles = (k1 - k0 + TILE - 1) // TILE
+        iters = (ntiles + kg - 1) // kg
+        need_lo, need_hi = max(kc0 - pr, 0), min(kc1 - 1 + pr, n - 1)
+        for it in range(iters):
+            key0 = k0 + it * kg * TILE
+            bad += key0 > need_hi
+            lim, lo = max(need_hi - key0, 0), max(need_lo - key0, 0)
+            for rel in range(kg * TILE):
+                row = max(min(rel, lim), lo)
+                bad += row < 0 or not (0 <= key0 + row < n)
+                bad += need_lo <= key0 + rel <= need_hi and row != rel
+    return bad
+
+
+@pytest.mark.parametrize("chunk_len", [512, 1024, 2048])
+@pytest.mark.parametrize("kg", [1, 2, 4])
+def test_row_clamp_stays_inside_the_needed_rows(chunk_len, kg):
+    for n in [1, 5, 31, 32, 33, 300, 511, 512, 513, 2047, 2048, 2049, 2080, 4096, 4099, 6000, 6145]:
+        for pool_r in [0, 1, 3, 16, 32]:
+            for halo, sweep in [(1, 2), (0, 2), (0, 1)]:
+                assert violations(n, chunk_len, kg, pool_r, halo, sweep) == 0, (n, pool_r, halo, sweep)
