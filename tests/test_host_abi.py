@@ -13,14 +13,6 @@ from paper_2407_11550_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-@pytest.fixture(scope="module")
-def lib():
-    if not os.path.exists(adakv.library_path()):
-        import __graft_entry__
-        __graft_entry__.build()
-    return adakv.load_library()
-
-
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "adakv.h")).read()
     names = set(re.findall(r"\b(adakv_[a-z_]+)\s*\(", header))

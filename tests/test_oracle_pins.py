@@ -390,7 +390,7 @@ def test_pyramid_budgets_sum_monotone_ratio_and_uniform_case():
     assert O.pyramid_budgets(4, 10, 3) == [16, 11, 8, 5]          # 15, 11.67, 8.33, 5: floors sum to 39, one unit to layer 0
 
 
-def test_pyramid_budgets_c_abi_matches_oracle():
+def test_pyramid_budgets_c_abi_matches_oracle(lib):
     import paper_2407_11550_amd as adakv
     for L, avg, ratio in [(32, 1024, 4.0), (32, 1000, 2.5), (7, 333, 10.0), (1, 50, 3.0), (2, 5, 9.0),
                           (80, 1024, 1.0), (64, 16384, 20.0), (3, 0, 2.0), (5, 7, 1.5)]:
