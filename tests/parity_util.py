@@ -66,7 +66,9 @@ def assert_end_to_end_close(out, ref, wl, b=0, seg0=0, row0=0):
     flat = np.sort(osc.reshape(-1))[::-1]
     if 0 < Bp < flat.size:
         tau = flat[Bp - 1]
-        near = int(((osc >= tau * (1 - BAND)) & (osc <= tau * (1 + BAND))).sum())
+        # sub-normal scores are flushed to zero on the GPU: the band gets the same absolute slack
+        # as the score comparison
+        near = int(((osc >= tau * (1 - BAND) - SCORE_ATOL) & (osc <= tau * (1 + BAND) + SCORE_ATOL)).sum())
     else:
         near = 0
     assert np.abs(g_bud - o_bud).sum() <= 2 * near + h, (g_bud, o_bud, near)
@@ -82,7 +84,7 @@ def assert_end_to_end_close(out, ref, wl, b=0, seg0=0, row0=0):
             continue
         v = np.sort(osc[c])[::-1]
         lo, hi = min(g_bud[c], o_bud[c]), max(g_bud[c], o_bud[c])
-        top = v[max(lo - 1, 0)] * (1 + BAND)
-        bot = v[min(hi, n - 1)] * (1 - BAND)
+        top = v[max(lo - 1, 0)] * (1 + BAND) + SCORE_ATOL
+        bot = v[min(hi, n - 1)] * (1 - BAND) - SCORE_ATOL
         for j in diff:
             assert bot <= osc[c, j] <= top, (c, j, osc[c, j], bot, top)

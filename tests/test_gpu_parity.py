@@ -305,3 +305,38 @@ def test_pipeline_flag_changes_nothing(case):
         assert torch.equal(a[key], b[key]), key
         assert torch.equal(a[key], c[key]), key
     assert int(a["budgets"].sum()) == sum(B) - w * h * len(n)
+
+
+def _fuzz_shapes():
+    """Forty seeded shapes across every dispatch branch of the scoring path (window rows per head
+    from 1 to 512, both head dimensions and dtypes, pool kernels 1 to 15, one to four ragged
+    sequences from a handful of tokens to several chunks, budgets from nothing to everything)."""
+    rng = np.random.default_rng(424242)
+    shapes = []
+    for i in range(40):
+        d = int(rng.choice([64, 128]))
+        g = int(rng.choice([1, 2, 3, 4, 8]))
+        h = int(rng.choice([1, 2, 4, 8]))
+        w = int(rng.choice([1, 2, 5, 8, 16, 32, 64]))
+        if g * w > 512:
+            w = 512 // g
+        k = int(rng.choice([1, 3, 5, 7, 9, 15]))
+        batch = int(rng.integers(1, 5))
+        top = int(rng.choice([40, 700, 2500, 7000, 20000]))
+        n = [int(rng.integers(1, top + 1)) for _ in range(batch)]
+        frac = float(rng.choice([0.0, 0.02, 0.1, 0.5, 1.0]))
+        B = [h * w + int(round(frac * h * nb)) for nb in n]
+        alpha = float(rng.choice([0.0, 0.2, 0.5, 1.0]))
+        dt = torch.float32 if (i % 5 == 4) else torch.bfloat16
+        shapes.append((g * h, h, d, w, k, n, B, alpha, dt, 500 + i))
+    return shapes
+
+
+def test_seeded_shape_sweep_matches_oracle():
+    for shape in _fuzz_shapes():
+        h_q, h, d, w, k, n, B, alpha, dt, seed = shape
+        _say(f"shape sweep {shape}")
+        wl = synth.small_workload(h_q, h, d, w, k, n, B, alpha=alpha, dtype=dt, seed=seed)
+        q, K, V = synth.generate(wl, device=DEV)
+        _, out = _run(wl, q, K, V)
+        _check_all(wl, q, K, V, out)
