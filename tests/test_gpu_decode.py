@@ -297,3 +297,40 @@ def test_eviction_loss_adaptive_against_uniform_allocation():
          f"retained weight {np.mean(kept[0.0]):.3f} / {np.mean(kept[0.2]):.3f} / {np.mean(kept[1.0]):.3f}")
     assert mean[0.0] < mean[1.0] and mean[0.2] < mean[1.0]
     assert sum(a < u for a, u in zip(losses[0.2], losses[1.0])) >= 5      # on most samples
+
+
+def test_seeded_decode_shape_sweep_matches_oracle():
+    """Twenty-four seeded shapes: group sizes 1 to 8, both head dimensions and dtypes, one to five
+    sequences, head-room 0 to 40, segments from the window alone to thousands of rows; two fused
+    steps each (the second works on the lengths the first one published)."""
+    rng = np.random.default_rng(77)
+    for i in range(24):
+        g = int(rng.choice([1, 2, 4, 8]))
+        h = int(rng.choice([1, 2, 4, 8]))
+        d = int(rng.choice([64, 128]))
+        w = int(rng.choice([1, 4, 32]))
+        dt = torch.float32 if i % 4 == 3 else torch.bfloat16
+        batch = int(rng.integers(1, 6))
+        top = int(rng.choice([30, 600, 5000]))
+        n = [int(rng.integers(2, top + 1)) for _ in range(batch)]
+        per_head = int(rng.integers(0, min(n) + 1))
+        hr = int(rng.choice([0, 1, 2, 40]))
+        shape = (g * h, h, d, w, n, per_head, dt, hr)
+        _say(f"decode sweep {shape}")
+        wl, layer, Kc, Vc, cu, seg_len = _decode_case(g * h, h, d, w, n, per_head, dt, hr, seed=300 + i,
+                                                      skew=float(rng.choice([0.0, 1.0, 2.5])))
+        qn, kn, vn = synth.decode_inputs(wl, 2, seed=300 + i, device=DEV)
+        oK, oV, olen = to_f64(Kc), to_f64(Vc), seg_len.cpu().numpy().astype(np.int64)
+        cuh = cu.cpu().numpy()
+        overflow = torch.zeros(1, dtype=torch.int32, device=DEV)
+        vmax = float(Vc.float().abs().max()) + 1.0
+        full = False
+        for t in range(2):
+            out, lse = adakv.decode_step(layer, qn[t], kn[t], vn[t], cu, hr, Kc, Vc, seg_len, overflow=overflow,
+                                         want_lse=True)
+            torch.cuda.synchronize()
+            full |= D.append(oK, oV, cuh, hr, olen, to_f64(kn[t]).reshape(-1, wl.d), to_f64(vn[t]).reshape(-1, wl.d))
+            assert np.array_equal(seg_len.cpu().numpy(), olen), (shape, t)
+            assert bool(overflow.item()) == full, (shape, t)
+            ref_out, ref_lse = D.decode_attention(to_f64(qn[t]), oK, oV, cuh, hr, olen, wl.g)
+            _assert_decode_close(out, lse, ref_out, ref_lse, vmax, f"{shape} step {t}")
