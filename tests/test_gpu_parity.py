@@ -340,3 +340,38 @@ def test_seeded_shape_sweep_matches_oracle():
         q, K, V = synth.generate(wl, device=DEV)
         _, out = _run(wl, q, K, V)
         _check_all(wl, q, K, V, out)
+
+
+def test_whole_step_replays_from_a_hip_graph():
+    """The four calls only enqueue kernels (no memset nodes, no allocation when the outputs and the
+    workspace are handed in), so a caller can capture them into a HIP graph.  Three replays with
+    eager work and synchronisations in between, on changing inputs, each checked against the
+    eager result."""
+    _say("graph replay")
+    wl = synth.small_workload(32, 8, 128, 32, 7, [5000, 1200], [8 * 200, 8 * 90], seed=31)
+    layer = adakv.Layer.from_workload(wl)
+    sets = [synth.generate(wl, layer=i, device=DEV) for i in range(3)]
+    q, K, V = [t.clone() for t in sets[0]]
+    ws = torch.empty(adakv.workspace_bytes(layer), dtype=torch.uint8, device=DEV)
+    bufs = dict(scores=torch.empty(layer.num_scores, dtype=torch.float32, device=DEV),
+                budgets=torch.empty(layer.num_segments, dtype=torch.int32, device=DEV),
+                cu_seqlens=torch.empty(layer.num_segments + 1, dtype=torch.int32, device=DEV),
+                indices=torch.empty(layer.num_rows_out, dtype=torch.int32, device=DEV),
+                K_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=DEV),
+                V_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=DEV))
+    adakv.compress(layer, q, K, V, ws=ws, bufs=bufs)             # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        adakv.compress(layer, q, K, V, ws=ws, bufs=bufs)
+    for i in (1, 2, 0):
+        for dst, src in zip((q, K, V), sets[i]):
+            dst.copy_(src)
+        eager = adakv.compress(layer, q, K, V)                   # fresh outputs, eager launches
+        torch.cuda.synchronize()
+        for t in bufs.values():
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for key in eager:
+            assert torch.equal(eager[key], bufs[key]), (i, key)
