@@ -71,6 +71,12 @@ typedef enum {
                                        the flag; breaking the promise gives undefined budgets and
                                        indices (no out-of-bounds access).                      */
 
+#define ADAKV_FLAG_POOL_THEN_MEAN 4u /* bit 2 of flags: adakv_score max-pools every window row along
+                                       the keys first and averages the g*w rows afterwards (Alg. 2
+                                       l.4 as printed) instead of averaging first (Section 3.4's
+                                       prose, the default).  Served by the plain-FMA kernels only
+                                       (far slower than the default path); pool_k/2 <= 100.     */
+
 /*
  * One attention layer's compression problem, for `batch` independent sequences (Algorithm 1
  * acts "within a single layer" of one sequence, so budgets never move between sequences).
@@ -115,7 +121,8 @@ const char *adakv_strerror(int status);
  * of Alg. 2 l.3 runs over the cache outside the window.  A caller that passes the prefill
  * attention's own log-sum-exp gets the normalisation over every visible key instead.
  * Logits are accumulated in fp32, softmax and reductions are fp32, the mean is taken before
- * the pool, and the pool is stride 1, same length, clipped at both ends.
+ * the pool (unless ADAKV_FLAG_POOL_THEN_MEAN asks for the other order: the max over j' then
+ * moves inside the sum over rows), and the pool is stride 1, same length, clipped at both ends.
  *
  *   q_window (device) [batch][h_q][w][d], contiguous, L->dtype
  *   K        (device) rows tok_off[b] .. tok_off[b]+n_b-1 are read, element (row, c, e) at

@@ -17,6 +17,7 @@ _lib = None
 
 ADAKV_BF16, ADAKV_FP32 = 0, 1
 ADAKV_FLAG_PIPELINE = 2
+ADAKV_FLAG_POOL_THEN_MEAN = 4
 MAX_BATCH = 64
 
 

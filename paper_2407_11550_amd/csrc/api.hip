@@ -67,8 +67,9 @@ static size_t topk_offset(const SeqTab &st, const Dims &dm, int dtype) {
 static size_t workspace_for(const SeqTab &st, const Dims &dm, int dtype) {
   return topk_offset(st, dm, dtype) + plan_topk_bytes(st, dm) + 256;
 }
+static bool pool_first(const adakv_layer *L) { return (L->flags & ADAKV_FLAG_POOL_THEN_MEAN) != 0; }
 static bool pipeline_mode(const adakv_layer *L, const Dims &dm) {
-  return (L->flags & ADAKV_FLAG_PIPELINE) != 0 && carry_supported(dm, L->dtype);
+  return (L->flags & ADAKV_FLAG_PIPELINE) != 0 && carry_supported(dm, L->dtype) && !pool_first(L);
 }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -166,12 +167,13 @@ int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   ScorePlan pl = plan_score(st, dm, L->dtype);
   hipStream_t s = (hipStream_t)hip_stream;
+  if (pool_first(L) && dm.pool_k / 2 > 100) return ADAKV_EUNSUPPORTED;
   TopkCarry tc = {nullptr, 0u, nullptr, nullptr};
   if (pipeline_mode(L, dm)) tc = plan_carry(st, dm, wsp + topk_offset(st, dm, L->dtype));
-  hipError_t e = mfma_path_supported(dm, L->dtype)
+  hipError_t e = (mfma_path_supported(dm, L->dtype) && !pool_first(L))
                      ? launch_score_mfma(st, dm, q_window, K, row_lse, scores, wsp, pl, tc, s)
                      : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
-                                            pl, s);
+                                            pl, pool_first(L), s);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 

@@ -69,7 +69,7 @@ bool mfma_path_supported(const Dims &dm, int dtype);
 
 hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, const void *q,
                                 const void *K, const float *row_lse, float *scores, char *ws,
-                                const ScorePlan &pl, hipStream_t s);
+                                const ScorePlan &pl, bool pool_first, hipStream_t s);
 hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
                              const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
                              const TopkCarry &tc, hipStream_t s);

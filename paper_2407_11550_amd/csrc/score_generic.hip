@@ -157,6 +157,56 @@ __global__ __launch_bounds__(256) void raw_generic_kernel(
   if (valid) raw[st.score_off[b] + (size_t)c * n + j] = acc * (1.0f / (float)R);
 }
 
+// The other order of Alg. 2 l.4 (as printed there): every window row is max-pooled along the keys
+// first, then the g*w rows of the head are averaged.  A block scores 256 consecutive keys and owns
+// the middle 256 - 2*radius of them, so that every owned key finds its pool window in LDS; keys
+// outside the sequence count as weight 0, which a max over non-negative weights never picks.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void pooled_generic_kernel(
+    SeqTab st, ChunkTab ct, Dims dm, const T *__restrict__ q, const T *__restrict__ K,
+    const float *__restrict__ lse, float *__restrict__ scores) {
+  __shared__ float qs[ROW_TILE][D];
+  __shared__ float sl[ROW_TILE];
+  __shared__ float ps[ROW_TILE][256];
+  const int tid = threadIdx.x;
+  const int b = find_seq(ct, st.batch, blockIdx.x);
+  const int chunk = blockIdx.x - ct.off[b];
+  const int c = blockIdx.y;
+  const int n = st.n[b];
+  const int R = dm.g * dm.w, RQ = dm.h_q * dm.w;
+  const int r = dm.pool_k / 2, own = 256 - 2 * r;      // the launcher guarantees own >= 1
+  const int j = chunk * own - r + tid;                 // the key this thread scores
+  const bool valid = j >= 0 && j < n;
+  const bool owner = tid >= r && tid < 256 - r && j < n;
+  float k[D];
+  if (valid) {
+    load_row<T, D>(K + (st.tok_off[b] + j) * dm.k_stride_tok + c * dm.k_stride_head, k);
+  } else {
+#pragma unroll
+    for (int e = 0; e < D; ++e) k[e] = 0.0f;
+  }
+  const T *qhead = q + ((size_t)b * RQ + (size_t)c * R) * D;
+  float acc = 0.0f;
+  for (int r0 = 0; r0 < R; r0 += ROW_TILE) {
+    __syncthreads();                                   // the previous tile's ps and qs are done with
+    stage_q<T, D>(qhead, r0, R, qs);
+    if (tid < ROW_TILE) sl[tid] = (r0 + tid < R) ? lse[(size_t)b * RQ + (size_t)c * R + r0 + tid] : 0.0f;
+    __syncthreads();
+    const int rt = min(ROW_TILE, R - r0);
+    for (int rr = 0; rr < rt; ++rr)
+      ps[rr][tid] = valid ? expf(logit<D>(qs[rr], k, dm.scale) - sl[rr]) : 0.0f;
+    __syncthreads();
+    if (owner) {
+      for (int rr = 0; rr < rt; ++rr) {
+        float m = ps[rr][tid - r];
+        for (int t = tid - r + 1; t <= tid + r; ++t) m = fmaxf(m, ps[rr][t]);
+        acc += m;
+      }
+    }
+  }
+  if (owner) scores[st.score_off[b] + (size_t)c * n + j] = acc * (1.0f / (float)R);
+}
+
 }  // namespace
 
 // lse[b][row] = log of the sum over the sequence's chunks of l * exp(m).  One wavefront per row:
@@ -236,7 +286,7 @@ void launch_pool(const SeqTab &st, const Dims &dm, const float *raw, float *scor
 template <typename T, int D>
 static void run_generic(const SeqTab &st, const Dims &dm, const void *q, const void *K,
                         const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-                        hipStream_t s) {
+                        bool pool_first, hipStream_t s) {
   const ChunkTab ct = make_chunks(st, GEN_CHUNK);
   dim3 grid(ct.off[st.batch], dm.h_kv), block(256);
   float *part_m = (float *)(ws + pl.part_m), *part_l = (float *)(ws + pl.part_l);
@@ -248,6 +298,12 @@ static void run_generic(const SeqTab &st, const Dims &dm, const void *q, const v
     launch_lse_combine(st, ct, dm.h_q * dm.w, part_m, part_l, lse, s);
     use_lse = lse;
   }
+  if (pool_first) {
+    const ChunkTab co = make_chunks(st, 256 - 2 * (dm.pool_k / 2));
+    ADAKV_LAUNCH("score_pooled_fma", (pooled_generic_kernel<T, D>), dim3(co.off[st.batch], dm.h_kv),
+                 block, s, st, co, dm, (const T *)q, (const T *)K, use_lse, scores);
+    return;
+  }
   ADAKV_LAUNCH("score_weights_fma", (raw_generic_kernel<T, D>), grid, block, s, st, ct, dm,
                (const T *)q, (const T *)K, use_lse, raw);
   launch_pool(st, dm, raw, scores, s);
@@ -255,13 +311,13 @@ static void run_generic(const SeqTab &st, const Dims &dm, const void *q, const v
 
 hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, const void *q,
                                 const void *K, const float *row_lse, float *scores, char *ws,
-                                const ScorePlan &pl, hipStream_t s) {
+                                const ScorePlan &pl, bool pool_first, hipStream_t s) {
   if (dtype == ADAKV_FP32) {
-    if (dm.d == 64) run_generic<float, 64>(st, dm, q, K, row_lse, scores, ws, pl, s);
-    else run_generic<float, 128>(st, dm, q, K, row_lse, scores, ws, pl, s);
+    if (dm.d == 64) run_generic<float, 64>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
+    else run_generic<float, 128>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
   } else {
-    if (dm.d == 64) run_generic<bf16_t, 64>(st, dm, q, K, row_lse, scores, ws, pl, s);
-    else run_generic<bf16_t, 128>(st, dm, q, K, row_lse, scores, ws, pl, s);
+    if (dm.d == 64) run_generic<bf16_t, 64>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
+    else run_generic<bf16_t, 128>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
   }
   return hipGetLastError();
 }

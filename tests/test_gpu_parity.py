@@ -375,3 +375,41 @@ def test_whole_step_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         for key in eager:
             assert torch.equal(eager[key], bufs[key]), (i, key)
+
+
+@pytest.mark.parametrize("case", [
+    (8, 2, 128, 8, 7, [3000, 41], torch.bfloat16, False),
+    (4, 4, 64, 8, 5, [1024], torch.float32, False),
+    (6, 2, 128, 5, 15, [700, 9, 260], torch.bfloat16, True),
+    (8, 8, 64, 2, 1, [500], torch.bfloat16, False),
+    (2, 1, 128, 3, 201, [333], torch.float32, False),      # the largest pool radius this order takes
+], ids=["bf16", "fp32", "row_lse", "no_pool", "radius100"])
+def test_pool_then_mean_flag_matches_oracle_order(case):
+    """ADAKV_FLAG_POOL_THEN_MEAN: scores follow the oracle's order="pool_then_mean"; the later
+    steps are exact functions of the scores as always."""
+    from paper_2407_11550_amd.binding import ADAKV_FLAG_POOL_THEN_MEAN
+    h_q, h, d, w, k, n, dt, with_lse = case
+    _say(f"pool then mean {case}")
+    B = [h * (w + max(1, nb // 10)) for nb in n]
+    wl = synth.small_workload(h_q, h, d, w, k, n, B, dtype=dt, seed=41)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl, flags=ADAKV_FLAG_POOL_THEN_MEAN)
+    lse = synth.prefill_row_lse(wl, q, K) if with_lse else None
+    out = adakv.compress(layer, q, K, V, row_lse=lse)
+    torch.cuda.synchronize()
+    off, soff, row0 = wl.tok_off, 0, 0
+    for b in range(wl.batch):
+        qd, Kd = to_f64(q[b]), to_f64(K[off[b]:off[b + 1]])
+        ref = O.score(qd, Kd, wl.n[b], w, k, order="pool_then_mean",
+                      row_lse=None if lse is None else to_f64(lse[b]))
+        ns = h * wl.n[b]
+        sc = out["scores"][soff:soff + ns].cpu().numpy()
+        assert_scores_close(sc, ref, f"pool then mean seq {b}")
+        assert_exact_on_scores(out, sc, wl, K, V, b, seg0=b * h, row0=row0)
+        soff += ns
+        row0 += wl.B[b]
+    plain = adakv.score(adakv.Layer.from_workload(wl), q, K, row_lse=lse)
+    if 1 < k <= 15:                                                     # (a pool window that always holds
+        assert not torch.equal(plain, out["scores"])                      # the head's peak hides the order)
+    elif k == 1:
+        assert_scores_close(plain.cpu().numpy(), out["scores"].cpu().numpy(), "orders agree without pooling")

@@ -398,3 +398,19 @@ def test_pyramid_budgets_c_abi_matches_oracle(lib):
     for bad in [(0, 10, 2.0), (4, -1, 2.0), (4, 10, 0.5), (4, 10, float("inf")), (4, 10, float("nan"))]:
         with pytest.raises(adakv.AdaKVError):
             adakv.pyramid_budgets(*bad)
+
+
+def test_pool_then_mean_order_against_library_pool_on_every_row():
+    """Alg. 2 l.4 as printed: pool each of the g*w rows, then average.  Library route: torch's
+    max_pool1d (stride 1, zero padding is harmless for non-negative weights) on the oracle's own
+    attention rows, then a plain mean."""
+    import torch
+    rng = np.random.default_rng(12)
+    h_q, h, d, w, n, k = 4, 2, 8, 3, 41, 5
+    q = rng.standard_normal((h_q, w, d)); K = rng.standard_normal((n + w, h, d))
+    A = O.attention_rows(q, K, n, w)                                     # [h_q, w, n]
+    rows = torch.from_numpy(A).reshape(h, (h_q // h) * w, n)
+    want = torch.nn.functional.max_pool1d(rows, k, stride=1, padding=k // 2).mean(dim=1).numpy()
+    got = O.score(q, K, n, w, k, order="pool_then_mean")
+    assert np.allclose(got, want.astype(np.float32), rtol=1e-6, atol=0)
+    assert not np.allclose(got, O.score(q, K, n, w, k), rtol=1e-3)       # the two orders really differ
