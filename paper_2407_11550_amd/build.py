@@ -32,5 +32,21 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return out
 
 
+def build_abi_driver(verbose: bool = False) -> str:
+    """tests/abi_driver: a plain C++ caller of the C ABI (hipMalloc, default stream, no Python),
+    linked against the library built above; used by one GPU test."""
+    src = os.path.join(ROOT, "tests", "abi_driver.cpp")
+    out = os.path.join(ROOT, "tests", "abi_driver.bin")
+    lib_dir = os.path.join(HERE, "lib")
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), src,
+           "-L", lib_dir, "-ladakv", "-Wl,-rpath,$ORIGIN/../paper_2407_11550_amd/lib", "-o", out]
+    if verbose:
+        print(" ".join(cmd))
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stdout + r.stderr)
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -413,3 +413,38 @@ def test_pool_then_mean_flag_matches_oracle_order(case):
         assert not torch.equal(plain, out["scores"])                      # the head's peak hides the order)
     elif k == 1:
         assert_scores_close(plain.cpu().numpy(), out["scores"].cpu().numpy(), "orders agree without pooling")
+
+
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float32], ids=["bf16", "fp32"])
+def test_c_abi_from_a_plain_cpp_program(dt, tmp_path):
+    """The library needs neither Python nor PyTorch: tests/abi_driver.bin (hipMalloc, default
+    stream) runs the four calls on files and its outputs are checked like the binding's."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi_driver.bin")
+    if not os.path.exists(exe):
+        pytest.fail("tests/abi_driver.bin is missing: run __graft_entry__.build()")
+    _say(f"abi_driver {dt}")
+    wl = synth.small_workload(8, 2, 128 if dt == torch.bfloat16 else 64, 16, 7, [2500, 310], [2 * 150, 2 * 40],
+                              dtype=dt, seed=71)
+    q, K, V = synth.generate(wl)                                    # on the host
+    raw = (lambda t: t.view(torch.int16).numpy()) if dt == torch.bfloat16 else (lambda t: t.numpy())
+    for name, t in (("q", q), ("K", K), ("V", V)):
+        raw(t.contiguous()).tofile(str(tmp_path / f"{name}.bin"))
+    code = 0 if dt == torch.bfloat16 else 1
+    meta = [code, wl.h_q, wl.h_kv, wl.d, wl.w, wl.pool_k, wl.alpha, 0, wl.batch] + wl.n + wl.B
+    (tmp_path / "meta.txt").write_text(" ".join(str(v) for v in meta) + "\n")
+    r = subprocess.run([exe, str(tmp_path)], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0, r.stdout + r.stderr
+    rows = sum(wl.B)
+    out = dict(scores=torch.from_numpy(np.fromfile(str(tmp_path / "scores.bin"), dtype=np.float32)),
+               budgets=torch.from_numpy(np.fromfile(str(tmp_path / "budgets.bin"), dtype=np.int32)),
+               cu_seqlens=torch.from_numpy(np.fromfile(str(tmp_path / "cu_seqlens.bin"), dtype=np.int32)),
+               indices=torch.from_numpy(np.fromfile(str(tmp_path / "indices.bin"), dtype=np.int32)))
+    for name in ("K_out", "V_out"):
+        if dt == torch.bfloat16:
+            t = torch.from_numpy(np.fromfile(str(tmp_path / f"{name}.bin"), dtype=np.int16)).view(torch.bfloat16)
+        else:
+            t = torch.from_numpy(np.fromfile(str(tmp_path / f"{name}.bin"), dtype=np.float32))
+        out[name] = t.view(rows, wl.d)
+    _check_all(wl, q, K, V, out)
