@@ -27,7 +27,8 @@ struct TopkWs {             // byte offsets inside the Top-k part of the workspa
   size_t hist_sel;          // u32 [3][batch*h][RADIX_BINS]  per-head digit counts, head scope
   size_t zero_end;          // everything before this starts at zero
   size_t state;             // uint2 [2][batch*h]: (digits chosen, rank left) after passes 0 and 1
-  size_t chunk_cnt;         // i32 [chunks][h][2]
+  size_t chunk_hist;        // u16 [chunks][h][1024]  head scope, last pass: each block's own digit counts
+  size_t chunk_sure;        // i32 [chunks][h]        ... and its elements above the threshold's 22-bit prefix
   size_t total;
 };
 
@@ -40,8 +41,9 @@ TopkWs plan(const SeqTab &st, const Dims &dm) {
   p.hist_sel = o; o += 3 * nseg * RADIX_BINS * 4;
   p.zero_end = o;
   p.state = o; o += align_up(2 * nseg * 8, 256);
-  p.chunk_cnt = o;
-  o += align_up((size_t)make_chunks(st, SEL_CHUNK).off[st.batch] * dm.h_kv * 2 * 4, 256);
+  const size_t blocks = (size_t)make_chunks(st, SEL_CHUNK).off[st.batch] * dm.h_kv;
+  p.chunk_hist = o; o += align_up(blocks * 1024 * 2, 256);
+  p.chunk_sure = o; o += align_up(blocks * 4, 256);
   p.total = o;
   return p;
 }
@@ -186,10 +188,14 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
                                                         const int *__restrict__ budgets,
                                                         HistSet hist,
                                                         unsigned *__restrict__ hist_tot,
-                                                        uint2 *__restrict__ state) {
+                                                        uint2 *__restrict__ state,
+                                                        unsigned short *__restrict__ chunk_hist,
+                                                        int *__restrict__ chunk_sure) {
   constexpr int NB = (P == 2) ? 1024 : RADIX_BINS;
+  constexpr bool LAST_HEAD_PASS = (P == 2) && !LAYER;   // also leaves what the emit kernel counts with
   __shared__ unsigned lh[RADIX_BINS];
   __shared__ unsigned sh[8];
+  __shared__ int sh_sure;
   const int tid = threadIdx.x;
   const int b = find_seq(ct, st.batch, blockIdx.x);
   const int chunk = blockIdx.x - ct.off[b];
@@ -206,17 +212,32 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
 #pragma unroll
   for (int i = 0; i < EPB; ++i) sc[i] = row[min(j0 + tid + 256 * i, j1 - 1)];
   for (int i = tid; i < NB; i += 256) lh[i] = 0u;
+  if (LAST_HEAD_PASS && tid == 0) sh_sure = 0;
   const Rank r = rank_before_pass<P, LAYER>(st, h, b, c, budgets, hist, hist_tot, state, sh);
   if (P >= 1 && chunk == 0 && (!LAYER || c == 0) && tid == 0)
     state[(size_t)(P - 1) * nsegs + (LAYER ? b : b * h + c)] = make_uint2(r.prefix, (unsigned)r.krem);
   __syncthreads();
   if (r.krem <= 0) return;                             // nothing to select in this segment
+  int sure = 0;
 #pragma unroll
   for (int i = 0; i < EPB; ++i) {
     const unsigned key = key_of(sc[i]);
-    if (j0 + tid + 256 * i < j1 && matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
+    const bool in = j0 + tid + 256 * i < j1;
+    if (in && matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
+    if (LAST_HEAD_PASS) sure += in && (key >> 10) > (r.prefix >> 10);
+  }
+  if (LAST_HEAD_PASS) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sure += __shfl_xor(sure, off);
+    if ((tid & 63) == 0) atomicAdd(&sh_sure, sure);
   }
   __syncthreads();
+  if (LAST_HEAD_PASS) {
+    // this block's own counts: the emit kernel adds up those of the chunks in front of its own
+    const size_t blk = (size_t)blockIdx.x * h + c;
+    for (int i = tid; i < 1024; i += 256) chunk_hist[blk * 1024 + i] = (unsigned short)lh[i];
+    if (tid == 0) chunk_sure[blk] = sh_sure;
+  }
   unsigned *gh = hist.p[P] + (size_t)(b * h + c) * RADIX_BINS;
   unsigned *gt = hist_tot + ((size_t)P * st.batch + b) * RADIX_BINS;
   for (int i = tid; i < NB; i += 256) {
@@ -376,42 +397,12 @@ __device__ __forceinline__ Rank head_threshold(const SeqTab &st, int h, int b, i
   return r;
 }
 
-__global__ __launch_bounds__(256) void emit_count_kernel(SeqTab st, ChunkTab ct, int h,
-                                                         const float *__restrict__ scores,
-                                                         HistSet hist,
-                                                         const uint2 *__restrict__ state,
-                                                         int *__restrict__ chunk_cnt) {
-  __shared__ unsigned sh[8];
-  __shared__ int tot[2];
-  const int tid = threadIdx.x;
-  const int b = find_seq(ct, st.batch, blockIdx.x);
-  const int chunk = blockIdx.x - ct.off[b];
-  const int c = blockIdx.y;
-  const int n = st.n[b];
-  if (tid < 2) tot[tid] = 0;
-  const Rank r = head_threshold(st, h, b, c, hist, state, sh);
-  const unsigned thr = r.prefix;
-  const float *row = scores + st.score_off[b] + (size_t)c * n;
-  __syncthreads();
-  int g = 0, e = 0;
-  const int j0 = chunk * SEL_CHUNK, j1 = min(n, j0 + SEL_CHUNK);
-  for (int j = j0 + tid; j < j1; j += 256) {
-    const unsigned key = key_of(row[j]);
-    g += key > thr;
-    e += key == thr;
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) { g += __shfl_xor(g, off); e += __shfl_xor(e, off); }
-  if ((tid & 63) == 0) { atomicAdd(&tot[0], g); atomicAdd(&tot[1], e); }
-  __syncthreads();
-  if (tid < 2) chunk_cnt[((size_t)blockIdx.x * h + c) * 2 + tid] = tot[tid];
-}
-
 __global__ __launch_bounds__(256) void emit_write_kernel(
     SeqTab st, ChunkTab ct, int h, int w, const float *__restrict__ scores,
     HistSet hist, const uint2 *__restrict__ state,
-    const int *__restrict__ chunk_cnt, const int *__restrict__ budgets,
-    const int *__restrict__ cu, int *__restrict__ indices, int rows_total) {
+    const unsigned short *__restrict__ chunk_hist, const int *__restrict__ chunk_sure,
+    const int *__restrict__ budgets, const int *__restrict__ cu, int *__restrict__ indices,
+    int rows_total) {
   __shared__ unsigned sh[8];
   __shared__ int sh_base[2];
   const int tid = threadIdx.x;
@@ -429,17 +420,51 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
 #pragma unroll
   for (int i = 0; i < EPT; ++i) keys[i] = (j0 + i < n) ? key_of(row[j0 + i]) : 0u;
 
-  // what the earlier chunks of this head hold above / at the threshold
+  // What the earlier chunks of this head hold above / at the threshold, from what the last
+  // histogram pass left per block: elements above the threshold's 22-bit prefix, and the counts
+  // of the last digit under that prefix (this thread looks at digits 4*tid .. 4*tid+3).  The loads
+  // do not depend on the threshold, so they are issued in front of its scan, 32 chunks at a time.
+  constexpr int CB = 32;   // 32 chunks = 131072 positions of a head in one round trip
   int pg = 0, pe = 0;
-  for (int k = tid; k < chunk; k += 256) {
-    const int *cc = chunk_cnt + ((size_t)(ct.off[b] + k) * h + c) * 2;
-    pg += cc[0];
-    pe += cc[1];
+  for (int k = tid; k < chunk; k += 256) pg += chunk_sure[(size_t)(ct.off[b] + k) * h + c];
+  uint2 first[CB];
+#pragma unroll
+  for (int u = 0; u < CB; ++u) {
+    const int k = min(u, max(chunk - 1, 0));
+    first[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(ct.off[b] + k) * h + c) * 1024 + tid * 4);
   }
   if (tid < 2) sh_base[tid] = 0;
   const Rank r = head_threshold(st, h, b, c, hist, state, sh);
   const unsigned thr = r.prefix;
   const int ties = r.krem;
+  const unsigned d2 = thr & 1023u;
+  auto add_counts = [&](const uint2 &v) {
+    const unsigned cnt[4] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned bin = (unsigned)tid * 4u + i;
+      pg += bin > d2 ? (int)cnt[i] : 0;
+      pe += bin == d2 ? (int)cnt[i] : 0;
+    }
+  };
+  if (thr == 0xFFFFFFFFu) {
+    pg = 0;                                            // nothing is selected in this head: the
+  } else {                                             // histogram pass left no counts behind
+#pragma unroll
+    for (int u = 0; u < CB; ++u)
+      if (u < chunk) add_counts(first[u]);
+    for (int k0c = CB; k0c < chunk; k0c += CB) {
+      uint2 more[CB];
+#pragma unroll
+      for (int u = 0; u < CB; ++u) {
+        const int k = min(k0c + u, chunk - 1);
+        more[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(ct.off[b] + k) * h + c) * 1024 + tid * 4);
+      }
+#pragma unroll
+      for (int u = 0; u < CB; ++u)
+        if (k0c + u < chunk) add_counts(more[u]);
+    }
+  }
   __syncthreads();
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) { pg += __shfl_xor(pg, off); pe += __shfl_xor(pe, off); }
@@ -524,7 +549,8 @@ static void run_passes(const SeqTab &st, const Dims &dm, const float *scores,
   dim3 grid(ct.off[st.batch], h), block(256);
 #define ADAKV_PASS(P)                                                                          \
   ADAKV_LAUNCH(LAYER ? "alloc_pass" #P : "select_pass" #P, (topk_hist_kernel<P, LAYER>), grid,   \
-               block, s, st, ct, h, scores, budgets_in, hist, hist_tot, state)
+               block, s, st, ct, h, scores, budgets_in, hist, hist_tot, state,                    \
+               (unsigned short *)(ws + p.chunk_hist), (int *)(ws + p.chunk_sure))
   if (!carried) {
     // this scope's own histograms (the layer scope's include the per-sequence totals)
     if (LAYER) launch_clear("alloc_init", (unsigned *)(ws + p.hist), (p.hist_sel - p.hist) / 4, s);
@@ -556,11 +582,9 @@ hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
   run_passes<false>(st, dm, scores, budgets, p, ct, ws, carried, s);
   const HistSet hist = hist_set(ws, p, st, dm, false, carried);
   dim3 grid(ct.off[st.batch], dm.h_kv), block(256);
-  ADAKV_LAUNCH("select_count", emit_count_kernel, grid, block, s, st, ct, dm.h_kv, scores, hist,
-               (const uint2 *)(ws + p.state), (int *)(ws + p.chunk_cnt));
   ADAKV_LAUNCH("select_emit", emit_write_kernel, grid, block, s, st, ct, dm.h_kv, dm.w, scores,
-               hist, (const uint2 *)(ws + p.state), (const int *)(ws + p.chunk_cnt), budgets,
-               cu_seqlens, indices, st.out_off[st.batch]);
+               hist, (const uint2 *)(ws + p.state), (const unsigned short *)(ws + p.chunk_hist),
+               (const int *)(ws + p.chunk_sure), budgets, cu_seqlens, indices, st.out_off[st.batch]);
   return hipGetLastError();
 }
 

@@ -259,7 +259,7 @@ def test_kernel_trace_names_every_kernel_and_costs_nothing_when_disarmed():
     torch.cuda.synchronize()
     names = [n for n, _ in tr.durations_us()]
     assert names[0].startswith("score_") and names[-1] == "compact"
-    assert sum(n.startswith("alloc_") for n in names) >= 3 and sum(n.startswith("select_") for n in names) >= 4
+    assert sum(n.startswith("alloc_") for n in names) >= 3 and sum(n.startswith("select_") for n in names) >= 3
     assert all(0 < us < 1e5 for _, us in tr.durations_us()) and tr.used == 2 * len(names)
     for key in ref:
         assert torch.equal(ref[key], out[key]), key
