@@ -28,7 +28,8 @@ struct TopkWs {             // byte offsets inside the Top-k part of the workspa
   size_t zero_end;          // everything before this starts at zero
   size_t state;             // uint2 [2][batch*h]: (digits chosen, rank left) after passes 0 and 1
   size_t chunk_hist;        // u16 [chunks][h][1024]  head scope, last pass: each block's own digit counts
-  size_t chunk_sure;        // i32 [chunks][h]        ... and its elements above the threshold's 22-bit prefix
+  size_t chunk_sure;        // i32 [chunks][h]        last pass of either scope: the block's elements above
+                            //                        the threshold's 22-bit prefix
   size_t total;
 };
 
@@ -193,6 +194,7 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
                                                         int *__restrict__ chunk_sure) {
   constexpr int NB = (P == 2) ? 1024 : RADIX_BINS;
   constexpr bool LAST_HEAD_PASS = (P == 2) && !LAYER;   // also leaves what the emit kernel counts with
+  constexpr bool LAST_LAYER_PASS = (P == 2) && LAYER;   // also counts what lies above the last bucket
   __shared__ unsigned lh[RADIX_BINS];
   __shared__ unsigned sh[8];
   __shared__ int sh_sure;
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
 #pragma unroll
   for (int i = 0; i < EPB; ++i) sc[i] = row[min(j0 + tid + 256 * i, j1 - 1)];
   for (int i = tid; i < NB; i += 256) lh[i] = 0u;
-  if (LAST_HEAD_PASS && tid == 0) sh_sure = 0;
+  if (P == 2 && tid == 0) sh_sure = 0;
   const Rank r = rank_before_pass<P, LAYER>(st, h, b, c, budgets, hist, hist_tot, state, sh);
   if (P >= 1 && chunk == 0 && (!LAYER || c == 0) && tid == 0)
     state[(size_t)(P - 1) * nsegs + (LAYER ? b : b * h + c)] = make_uint2(r.prefix, (unsigned)r.krem);
@@ -224,9 +226,9 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
     const unsigned key = key_of(sc[i]);
     const bool in = j0 + tid + 256 * i < j1;
     if (in && matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
-    if (LAST_HEAD_PASS) sure += in && (key >> 10) > (r.prefix >> 10);
+    if (P == 2) sure += in && (key >> 10) > (r.prefix >> 10);
   }
-  if (LAST_HEAD_PASS) {
+  if (P == 2) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) sure += __shfl_xor(sure, off);
     if ((tid & 63) == 0) atomicAdd(&sh_sure, sure);
@@ -238,12 +240,15 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
     for (int i = tid; i < 1024; i += 256) chunk_hist[blk * 1024 + i] = (unsigned short)lh[i];
     if (tid == 0) chunk_sure[blk] = sh_sure;
   }
+  // layer scope: one plain store per block, the finishing kernel adds a head's blocks up
+  if (LAST_LAYER_PASS && tid == 0) chunk_sure[(size_t)blockIdx.x * h + c] = sh_sure;
   unsigned *gh = hist.p[P] + (size_t)(b * h + c) * RADIX_BINS;
   unsigned *gt = hist_tot + ((size_t)P * st.batch + b) * RADIX_BINS;
   for (int i = tid; i < NB; i += 256) {
     const unsigned v = lh[i];
     if (v) {
-      atomicAdd(&gh[i], v);
+      // the layer scope looks at per-head counts only after its last pass
+      if (!LAYER || P == 2) atomicAdd(&gh[i], v);
       if (LAYER) atomicAdd(&gt[i], v);
     }
   }
@@ -251,9 +256,11 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
 
 // Layer scope, after the third pass: Algorithm 1's counts f_c and the safeguard of Alg. 2 l.8.
 // One block of eight wavefronts per sequence.
-__global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, int h, int w, int alpha_fix,
+__global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, ChunkTab ct, int h, int w,
+                                                           int alpha_fix,
                                                            HistSet hist,
                                                            const unsigned *__restrict__ hist_tot,
+                                                           const int *__restrict__ chunk_sure,
                                                            const uint2 *__restrict__ state,
                                                            int *__restrict__ budgets,
                                                            int *__restrict__ cu) {
@@ -263,20 +270,20 @@ __global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, int h, int
   const int b = blockIdx.x;
   const int nsegs = st.batch * h;
   if (tid < 64) { sh_gt[tid] = 0; sh_eq[tid] = 0; }
-  // Wavefront wv takes heads wv, wv+8, ...; a lane loads all its bins of the three histograms
-  // of a head at once (20 independent 16-byte loads).  The first head's loads are issued before
-  // the threshold is known (they do not depend on it), so they share its round trip.
-  struct HeadBins { uint4 v0[8], v1[8], v2[4]; };
+  // Wavefront wv takes heads wv, wv+8, ...: the last pass's digit counts of the head (a lane
+  // loads its 16 bins at once) and the number of its elements above the threshold's 22-bit
+  // prefix, which the last histogram pass counted.  The first head's loads are issued before the
+  // threshold is known (they do not depend on it), so they share its round trip.
+  struct HeadBins { uint4 v2[4]; int sure; };
   auto load_head = [&](int c) {
     HeadBins hb;
     const int cc = min(c, h - 1);
-    const uint4 *b0 = reinterpret_cast<const uint4 *>(hist.p[0] + (size_t)(b * h + cc) * RADIX_BINS) + lane * 8;
-    const uint4 *b1 = reinterpret_cast<const uint4 *>(hist.p[1] + (size_t)(b * h + cc) * RADIX_BINS) + lane * 8;
     const uint4 *b2 = reinterpret_cast<const uint4 *>(hist.p[2] + (size_t)(b * h + cc) * RADIX_BINS) + lane * 4;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { hb.v0[i] = b0[i]; hb.v1[i] = b1[i]; }
-#pragma unroll
     for (int i = 0; i < 4; ++i) hb.v2[i] = b2[i];
+    int sure = 0;                                      // the lanes stride over the head's blocks
+    for (int k = ct.off[b] + lane; k < ct.off[b + 1]; k += 64) sure += chunk_sure[(size_t)k * h + cc];
+    hb.sure = sure;
     return hb;
   };
   HeadBins first = load_head(wv);
@@ -284,23 +291,12 @@ __global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, int h, int
   __syncthreads();
   // r.prefix is the threshold key, r.krem how many threshold-valued elements are taken (in
   // flat-index order, i.e. head by head).  Per head: elements strictly above the threshold are
-  // those in higher bins of pass 0, plus higher bins of pass 1 under the same first digit, ...
+  // those above its 22-bit prefix plus those under the prefix with a larger last digit.
   if (r.krem > 0) {
-    const unsigned d0 = digit_of<0>(r.prefix), d1 = digit_of<1>(r.prefix), d2 = digit_of<2>(r.prefix);
+    const unsigned d2 = digit_of<2>(r.prefix);
     for (int c = wv; c < h; c += 8) {
       const HeadBins hb = (c == wv) ? first : load_head(c);
       int cnt = 0, eq = 0;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const unsigned a0[4] = {hb.v0[i].x, hb.v0[i].y, hb.v0[i].z, hb.v0[i].w};
-        const unsigned a1[4] = {hb.v1[i].x, hb.v1[i].y, hb.v1[i].z, hb.v1[i].w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const unsigned bin = (unsigned)(lane * 32 + i * 4 + k);
-          if (bin > d0) cnt += (int)a0[k];
-          if (bin > d1) cnt += (int)a1[k];
-        }
-      }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const unsigned a2[4] = {hb.v2[i].x, hb.v2[i].y, hb.v2[i].z, hb.v2[i].w};
@@ -311,6 +307,7 @@ __global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, int h, int
           if (bin == d2) eq += (int)a2[k];
         }
       }
+      cnt += hb.sure;
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1) { cnt += __shfl_xor(cnt, off); eq += __shfl_xor(eq, off); }
       if (lane == 0) { sh_gt[c] = cnt; sh_eq[c] = eq; }
@@ -567,10 +564,10 @@ hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
   run_passes<true>(st, dm, scores, nullptr, p, ct, ws, carried, s);
-  ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(512), s, st, dm.h_kv,
+  ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(512), s, st, ct, dm.h_kv,
                dm.w, dm.alpha_fix, hist_set(ws, p, st, dm, true, carried),
-               (const unsigned *)(ws + p.hist_tot), (const uint2 *)(ws + p.state), budgets,
-               cu_seqlens);
+               (const unsigned *)(ws + p.hist_tot), (const int *)(ws + p.chunk_sure),
+               (const uint2 *)(ws + p.state), budgets, cu_seqlens);
   return hipGetLastError();
 }
 
