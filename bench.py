@@ -50,6 +50,28 @@ def algorithmic_bytes(wl, kept_rows):
             "compact": gather + kept_rows * 4, "k_stream": k_stream}
 
 
+def traced_pass(adakv, torch, step, n_steps, kernels_per_step):
+    """Per-kernel durations from event pairs attached to the launches.  Steps run back to back
+    inside one trace (as many as its 256 events hold) with one synchronisation per batch, so the
+    kernels are timed in the same stream of work as in the throughput measurement."""
+    per_kernel, order = {}, []
+    batch = max(1, 256 // (2 * kernels_per_step))
+    done = 0
+    while done < n_steps:
+        todo = min(batch, n_steps - done)
+        with adakv.KernelTrace(256) as tr:
+            for i in range(done, done + todo):
+                step(i)
+        torch.cuda.synchronize()
+        for name, us in tr.durations_us():
+            if name not in per_kernel:
+                per_kernel[name] = []
+                order.append(name)
+            per_kernel[name].append(us)
+        done += todo
+    return per_kernel, order
+
+
 def calibrate_copy(torch, dev):
     """Three 1 GiB device-to-device copies: a known number of bytes for scaling rocprofv3's
     FETCH_SIZE / WRITE_SIZE counters."""
@@ -110,16 +132,7 @@ def bench_decode(args):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = 1000.0 * (t1 - t0) / args.steps
-    per_kernel, order = {}, []
-    for i in range(trace_steps):
-        with adakv.KernelTrace(16) as tr:
-            step(i)
-        torch.cuda.synchronize()
-        for name, us in tr.durations_us():
-            if name not in per_kernel:
-                per_kernel[name] = []
-                order.append(name)
-            per_kernel[name].append(us)
+    per_kernel, order = traced_pass(adakv, torch, step, trace_steps, kernels_per_step=2)
     assert int(overflow.item()) == 0, "head-room too small for the number of steps"
     kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
     esz = 2 if str(wl.dtype).endswith("bfloat16") else 4
@@ -233,18 +246,8 @@ def main():
     value = tokens / (ms_per_step * 1e-3)
 
     # ---- per-kernel durations, live, events on the launch stream (a second pass) ------------
-    per_kernel = {}
-    order = []
     trace_steps = min(args.steps, 50)
-    for i in range(trace_steps):
-        with adakv.KernelTrace(64) as tr:
-            step(i)
-        torch.cuda.synchronize()
-        for name, us in tr.durations_us():
-            if name not in per_kernel:
-                per_kernel[name] = []
-                order.append(name)
-            per_kernel[name].append(us)
+    per_kernel, order = traced_pass(adakv, torch, step, trace_steps, kernels_per_step=16)
     kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
     kept = layer.num_rows_out
     alg = algorithmic_bytes(wl, kept)
