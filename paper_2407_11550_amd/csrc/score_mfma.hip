@@ -203,19 +203,21 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
       const int qi = tid % RPAD, sl = tid / RPAD;
       float M = -INFINITY, L = 0.0f;
       if (qi < R) {
-        // eight chunks' partials are loaded at a time (one round trip), then folded in
+        // CB chunks' partials are loaded at a time (one round trip: nothing else is live in the
+        // registers yet, and the main loop cannot start before this is done), then folded in
+        constexpr int CB = 32;
         const int kend = ct.off[b + 1];
-        for (int k0c = ct.off[b] + sl; k0c < kend; k0c += 8 * SL) {
-          float pm[8], pl[8];
+        for (int k0c = ct.off[b] + sl; k0c < kend; k0c += CB * SL) {
+          float pm[CB], pl[CB];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
+          for (int u = 0; u < CB; ++u) {
             const int k = min(k0c + u * SL, kend - 1);
             const size_t o = (size_t)k * RQ + (size_t)c * R + qi;
             pm[u] = part_m[o];
             pl[u] = part_l[o];
           }
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
+          for (int u = 0; u < CB; ++u) {
             if (k0c + u * SL < kend) {
               const float m = pm[u] * LOG2E;
               const float nm = fmaxf(M, m);
