@@ -15,6 +15,13 @@
 // kernel, whose every block scans the (small) finished histogram in its prologue.  A kernel
 // boundary is the cheapest device-wide synchronisation on this part: a device-scope fence
 // inside a kernel writes a whole L2 back.
+//
+// Kernels per call: [clear, pass 0,] pass 1, pass 2, then alloc_finish (layer scope) or
+// emit_write (head scope).  The bracketed two are skipped in pipeline mode, where the scoring
+// kernels have cleared the histograms and counted the first digits (which do not depend on the
+// scope).  The last pass also leaves per-block counts behind (elements above the threshold's
+// 22-bit prefix; head scope: the block's own last-digit histogram), so that the kernel after it
+// does not have to read the scores once more just to count.
 #include "common.h"
 
 namespace adakv {
