@@ -187,6 +187,10 @@ def main():
     ap.add_argument("--alpha", type=float, default=None)
     ap.add_argument("--sets", type=int, default=5, help="distinct input sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="compress path: issue the layer calls round-robin on this many streams (each with "
+                         "its own workspace and outputs), so that one layer's latency-bound selection kernels "
+                         "run beside the next layer's sweeps; 1 (the default, the headline) = one layer at a time")
     ap.add_argument("--row-lse", action="store_true",
                     help="compress path: hand adakv_score the prefill attention's row log-sum-exp, "
                          "which removes the statistics sweep (not the headline configuration)")
@@ -218,20 +222,28 @@ def main():
     layer = adakv.Layer.from_workload(wl)
     sets = [synth.generate(wl, layer=i, device=dev) for i in range(args.sets)]
     lses = [synth.prefill_row_lse(wl, q, K) if args.row_lse else None for q, K, _ in sets]
-    ws = torch.empty(adakv.workspace_bytes(layer), dtype=torch.uint8, device=dev)
-    bufs = dict(scores=torch.empty(layer.num_scores, dtype=torch.float32, device=dev),
-                budgets=torch.empty(layer.num_segments, dtype=torch.int32, device=dev),
-                cu_seqlens=torch.empty(layer.num_segments + 1, dtype=torch.int32, device=dev),
-                indices=torch.empty(layer.num_rows_out, dtype=torch.int32, device=dev),
-                K_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev),
-                V_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev))
+    def make_bufs():
+        return (torch.empty(adakv.workspace_bytes(layer), dtype=torch.uint8, device=dev),
+                dict(scores=torch.empty(layer.num_scores, dtype=torch.float32, device=dev),
+                     budgets=torch.empty(layer.num_segments, dtype=torch.int32, device=dev),
+                     cu_seqlens=torch.empty(layer.num_segments + 1, dtype=torch.int32, device=dev),
+                     indices=torch.empty(layer.num_rows_out, dtype=torch.int32, device=dev),
+                     K_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev),
+                     V_out=torch.empty((layer.num_rows_out, wl.d), dtype=wl.dtype, device=dev)))
+
+    # one workspace and one set of outputs per stream: calls that share them must be ordered
+    lanes = [make_bufs() for _ in range(max(1, args.streams))]
+    streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else [None]
+    ws, bufs = lanes[0]
 
     if args.calibrate_copy:
         calibrate_copy(torch, dev)
 
     def step(i):
         q, K, V = sets[i % len(sets)]
-        return adakv.compress(layer, q, K, V, row_lse=lses[i % len(sets)], ws=ws, bufs=bufs)
+        lane_ws, lane_bufs = lanes[i % len(lanes)]
+        return adakv.compress(layer, q, K, V, row_lse=lses[i % len(sets)], ws=lane_ws, bufs=lane_bufs,
+                              stream=streams[i % len(streams)])
 
     for i in range(args.warmup):
         step(i)
@@ -306,7 +318,8 @@ def main():
         "config": {"workload": wl.name, "h_q": wl.h_q, "h_kv": wl.h_kv, "d": wl.d, "n": wl.n,
                    "w": wl.w, "pool_k": wl.pool_k, "B": wl.B, "alpha": wl.alpha, "batch": wl.batch,
                    "input_sets_rotated": len(sets),
-                   "row_lse": "supplied by the caller (single sweep)" if args.row_lse else "computed (two sweeps)"},
+                   "row_lse": "supplied by the caller (single sweep)" if args.row_lse else "computed (two sweeps)",
+                   "layers_in_flight": max(1, args.streams)},
         "pipeline_hbm_frac": round(total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "pipeline_algorithmic_bytes": total_alg,
         "score_mfma_tflops": round(flops / (sum(v for k, v in kernels.items() if k.startswith("score_")) * 1e-6) / 1e12, 2),
