@@ -448,3 +448,24 @@ def test_c_abi_from_a_plain_cpp_program(dt, tmp_path):
             t = torch.from_numpy(np.fromfile(str(tmp_path / f"{name}.bin"), dtype=np.float32))
         out[name] = t.view(rows, wl.d)
     _check_all(wl, q, K, V, out)
+
+
+def test_side_stream_and_unaligned_workspace_give_the_same_result():
+    """Calls only enqueue on the stream they are given, and the workspace may start anywhere."""
+    _say("side stream, unaligned workspace")
+    wl = synth.small_workload(16, 4, 128, 16, 7, [2600, 900], [4 * 100, 4 * 60], seed=55)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl)
+    ref = adakv.compress(layer, q, K, V)
+    torch.cuda.synchronize()
+    big = torch.empty(adakv.workspace_bytes(layer) + 64, dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    out = adakv.compress(layer, q, K, V, ws=big[24:], stream=side)
+    side.synchronize()
+    for key in ref:
+        assert torch.equal(ref[key], out[key]), key
+    # a workspace that is too small is refused before anything is launched
+    with pytest.raises(adakv.AdaKVError) as e:
+        adakv.score(layer, q, K, ws=big[:1000])
+    assert e.value.status == -3
