@@ -109,8 +109,16 @@ __device__ __forceinline__ int scan_blocks(int nseg, int per, int split, int hea
 }
 
 // ---------------------------------------------------------------------------------------------
+// Query heads one wavefront carries: at most four (queries and accumulators take 2*GW*EPL
+// registers).  A larger group is split over NGRP sets of four wavefronts that read the
+// same rows at the same time (the second read of a row is a cache hit).
+template <typename T, int G> struct HeadSplit {
+  static constexpr int GW = G > 4 ? 4 : G;
+  static constexpr int NGRP = G / GW;
+};
+
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void decode_attn_kernel(
+__global__ __launch_bounds__((256 * HeadSplit<T, G>::NGRP)) void decode_attn_kernel(
     int nseg, int h, int per, int split, int headroom, float c_log2, const T *__restrict__ q,
     const char *__restrict__ k_new, const char *__restrict__ v_new, const int *__restrict__ cu,
     const int *__restrict__ seg_len, char *Kc, char *Vc, float *__restrict__ part_acc,
@@ -119,18 +127,18 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
   constexpr int ROWB = D * (int)sizeof(T);
   constexpr int LPR = ROWB / 16;               // lanes per row
   constexpr int RPW = 64 / LPR;                // rows per wavefront load
-  constexpr int NW = 4;
-  // With many query rows per KV head the widened queries alone would take G*EPL registers: they
-  // then stay packed as loaded and are widened at every use, and fewer row loads are in flight.
-  constexpr bool PACKQ = G * EPL > 32;
-  constexpr int U = PACKQ ? 2 : 4;             // row loads in flight per lane, for K and for V
+  constexpr int NW = 4;                        // wavefronts that share the rows of a split
+  constexpr int GW = HeadSplit<T, G>::GW, NGRP = HeadSplit<T, G>::NGRP;
+  constexpr int NT = 256 * NGRP;
+  constexpr int U = 4;                         // row loads in flight per lane, for K and for V
 
-  __shared__ int sh_scan[12];
+  __shared__ int sh_scan[24];                  // [0..15] the prefix sum's wavefront totals, [16..20] results
   __shared__ float sh_acc[NW][G][D];
   __shared__ float sh_m[NW][G], sh_l[NW][G];
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wv_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wv_all / NW, wv = wv_all % NW; // head set, and place among the set's wavefronts
   const int col = lane % LPR, slot = lane / LPR;
 
   // ---- which (segment, split) is this workgroup? -------------------------------------------
@@ -138,7 +146,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
   // the row is taken from k_new/v_new by the lanes it falls to, which also store it in the cache.
   const int grow = k_new != nullptr ? 1 : 0;
   int total;
-  const int excl = scan_blocks(nseg, per, split, headroom, grow, cu, seg_len, sh_scan, &total);
+  const int excl = scan_blocks<NW * NGRP>(nseg, per, split, headroom, grow, cu, seg_len, sh_scan, &total);
   {
     int first = excl;
     for (int i = 0; i < per; ++i) {
@@ -147,11 +155,11 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
       const int now = rows_held(cu, seg_len, s, headroom, grow);
       const int nb = (now + split - 1) / split;
       if ((int)blockIdx.x >= first && (int)blockIdx.x < first + nb) {
-        sh_scan[4] = s;
-        sh_scan[5] = (int)blockIdx.x - first;
-        sh_scan[6] = now;
-        sh_scan[7] = cu[s];
-        sh_scan[8] = now - rows_held(cu, seg_len, s, headroom, 0);   // 1: the last row is the new one
+        sh_scan[16] = s;
+        sh_scan[17] = (int)blockIdx.x - first;
+        sh_scan[18] = now;
+        sh_scan[19] = cu[s];
+        sh_scan[20] = now - rows_held(cu, seg_len, s, headroom, 0);  // 1: the last row is the new one
       }
       // the merge kernel finds a segment's partial results through this table; the launch has at
       // least one workgroup per segment, and workgroup s files the entry of segment s
@@ -162,34 +170,28 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
   }
   if ((int)blockIdx.x >= total) return;        // uniform: the launch is an upper bound
   __syncthreads();
-  const int s = sh_scan[4], j = sh_scan[5], len = sh_scan[6];
+  const int s = sh_scan[16], j = sh_scan[17], len = sh_scan[18];
   const int b = s / h, c = s % h;
   const int r0 = j * split, r1 = min(len, r0 + split);
-  const int new_row = sh_scan[8] ? len - 1 : -1;
-  const long long seg_byte = ((long long)sh_scan[7] + (long long)s * headroom) * ROWB + col * 16;
+  const int new_row = sh_scan[20] ? len - 1 : -1;
+  const long long seg_byte = ((long long)sh_scan[19] + (long long)s * headroom) * ROWB + col * 16;
   char *Kb = Kc + seg_byte;
   char *Vb = Vc + seg_byte;
   const long long new_byte = (long long)s * ROWB + col * 16;
 
   // ---- the g query rows of this KV head, pre-scaled so that exp() becomes exp2() --------------
-  float qf[PACKQ ? 1 : G][EPL];
-  u32x4 qp16[PACKQ ? G : 1];
+  float qf[GW][EPL];
 #pragma unroll
-  for (int gi = 0; gi < G; ++gi) {
-    const T *qp = q + ((long long)(b * h + c) * G + gi) * D + col * EPL;
-    const u32x4 raw = *reinterpret_cast<const u32x4 *>(qp);
-    if constexpr (PACKQ) {
-      qp16[gi] = raw;
-    } else {
-      Elem<T>::widen(raw, qf[gi]);
+  for (int gi = 0; gi < GW; ++gi) {
+    const T *qp = q + ((long long)(b * h + c) * G + grp * GW + gi) * D + col * EPL;
+    Elem<T>::widen(*reinterpret_cast<const u32x4 *>(qp), qf[gi]);
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) qf[gi][e] *= c_log2;
-    }
+    for (int e = 0; e < EPL; ++e) qf[gi][e] *= c_log2;
   }
 
-  float m[G], l[G], acc[G][EPL];
+  float m[GW], l[GW], acc[GW][EPL];
 #pragma unroll
-  for (int gi = 0; gi < G; ++gi) {
+  for (int gi = 0; gi < GW; ++gi) {
     m[gi] = M_INIT; l[gi] = 0.0f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[gi][e] = 0.0f;
@@ -211,38 +213,28 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
       const bool fresh = rr == new_row;
       kk[u] = *reinterpret_cast<const u32x4 *>(fresh ? k_new + new_byte : Kb + o);
       vv[u] = *reinterpret_cast<const u32x4 *>(fresh ? v_new + new_byte : Vb + o);
-      if (r == new_row) {
+      if (r == new_row && grp == 0) {
         *reinterpret_cast<u32x4 *>(Kb + o) = kk[u];
         *reinterpret_cast<u32x4 *>(Vb + o) = vv[u];
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[EPL], sc[G];
+      float kf[EPL], sc[GW];
       Elem<T>::widen(kk[u], kf);
       bool grow = false;
 #pragma unroll
-      for (int gi = 0; gi < G; ++gi) {
+      for (int gi = 0; gi < GW; ++gi) {
         float a = 0.0f;
-        if constexpr (PACKQ) {
-          float qw[EPL];
-          u32x4 packed = qp16[gi];
-          asm volatile("" : "+v"(packed));     // keeps the widening inside the loop
-          Elem<T>::widen(packed, qw);
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) a = fmaf(qw[e], kf[e], a);
-          a *= c_log2;
-        } else {
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) a = fmaf(qf[gi][e], kf[e], a);
-        }
+        for (int e = 0; e < EPL; ++e) a = fmaf(qf[gi][e], kf[e], a);
         a = row_sum<LPR>(a);
         sc[gi] = ok[u] ? a : -INFINITY;
         grow |= sc[gi] > m[gi];
       }
       if (__any(grow)) {                       // a new running maximum somewhere in the wavefront
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi) {
+        for (int gi = 0; gi < GW; ++gi) {
           const float mn = fmaxf(m[gi], sc[gi]);
           const float corr = fast_exp2(m[gi] - mn);
           l[gi] *= corr;
@@ -254,7 +246,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
       float vf[EPL];
       Elem<T>::widen(vv[u], vf);
 #pragma unroll
-      for (int gi = 0; gi < G; ++gi) {
+      for (int gi = 0; gi < GW; ++gi) {
         const float p = fast_exp2(sc[gi] - m[gi]);
         l[gi] += p;
 #pragma unroll
@@ -263,9 +255,9 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
     }
   }
 
-  // ---- merge the RPW row slots of the wavefront, then the NW wavefronts ----------------------
+  // ---- merge the RPW row slots of the wavefront, then the NW wavefronts of each head set --------
 #pragma unroll
-  for (int gi = 0; gi < G; ++gi) {
+  for (int gi = 0; gi < GW; ++gi) {
     float M = m[gi];
 #pragma unroll
     for (int o = LPR; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
@@ -281,13 +273,14 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
       acc[gi][e] = a;
     }
     if (slot == 0) {
+      const int head = grp * GW + gi;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) sh_acc[wv][gi][col * EPL + e] = acc[gi][e];
-      if (col == 0) { sh_m[wv][gi] = M; sh_l[wv][gi] = ll; }
+      for (int e = 0; e < EPL; ++e) sh_acc[wv][head][col * EPL + e] = acc[gi][e];
+      if (col == 0) { sh_m[wv][head] = M; sh_l[wv][head] = ll; }
     }
   }
   __syncthreads();
-  for (int t = tid; t < G * D; t += 256) {
+  for (int t = tid; t < G * D; t += NT) {
     const int gi = t / D, e = t % D;
     float M = sh_m[0][gi];
 #pragma unroll
@@ -406,7 +399,8 @@ void run_decode(const SeqTab &st, const Dims &dm, int headroom, const DecodePlan
   float *part_acc = (float *)(ws + pl.part_acc);
   float *part_ml = (float *)(ws + pl.part_ml);
   int4 *seg_tab = (int4 *)(ws + pl.seg_tab);
-  ADAKV_LAUNCH("decode_attn", (decode_attn_kernel<T, D, G>), dim3(pl.nblk), dim3(256), s, nseg,
+  ADAKV_LAUNCH("decode_attn", (decode_attn_kernel<T, D, G>), dim3(pl.nblk),
+               dim3(256 * HeadSplit<T, G>::NGRP), s, nseg,
                dm.h_kv, per, pl.split, headroom, dm.scale * LOG2E, (const T *)q,
                (const char *)k_new, (const char *)v_new, cu, (const int *)seg_len, (char *)Kc,
                (char *)Vc, part_acc, part_ml, seg_tab);
