@@ -6,8 +6,8 @@
 // be added up, so K is swept twice:
 //   sweep 1 (PASS 1)  per-row (max, sum of exp) over the keys        -> partial statistics
 //   sweep 2 (PASS 2)  exp(logit - lse) summed over the g*w rows      -> pre-pool scores
-// Sweep 2 walks the key chunks in the opposite order, so it starts on what sweep 1 left in the
-// memory-side cache.  A caller-supplied row_lse skips sweep 1.
+// Sweep 2 walks every chunk backwards from the point where sweep 1 started (and ended) it, so it
+// begins with what sweep 1 left in the memory-side cache.  A caller-supplied row_lse skips sweep 1.
 //
 // Work split.  A workgroup owns CHUNK consecutive keys of one KV head; all g query heads of the
 // group share every K tile.  A wavefront keeps at most 64 window rows of Q in registers as MFMA
@@ -140,7 +140,22 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // channels.  Each workgroup therefore starts at a different point of its chunk and wraps
   // around (neither sweep depends on the order of the tiles).
   const int rot = (int)(((long long)chunk * iters) / (ct.off[b + 1] - ct.off[b]));
-  auto phys = [&](int it) { const int p = it + rot; return p >= iters ? p - iters : p; };
+#ifndef ADAKV_SWEEP2_BACKWARDS
+#define ADAKV_SWEEP2_BACKWARDS 1
+#endif
+  // Sweep 1 walks its chunk forwards from the rotated start; sweep 2 walks it backwards from
+  // there, i.e. it begins with what sweep 1 read last.  Both sweeps have every chunk in flight
+  // at once, so this, and not the order of the chunks, decides what the memory-side cache still
+  // holds: reading a set slightly larger than a cache twice in the same direction hits nothing,
+  // reading it back hits most of it.
+  auto phys = [&](int it) {
+    if (PASS == 2 && ADAKV_SWEEP2_BACKWARDS) {
+      const int p = rot - 1 - it;
+      return p < 0 ? p + iters : p;
+    }
+    const int p = it + rot;
+    return p >= iters ? p - iters : p;
+  };
 
   // Branch-free on purpose (the compiler can only keep older loads in flight across a wait if
   // the loads in between are issued on every path).  Rows are clamped into the range somebody
