@@ -41,7 +41,7 @@ MEASURED_TRAFFIC_BYTES = {
 def algorithmic_bytes(wl, kept_rows):
     """Bytes the path has to move per layer call, per stage (one read of K for scoring, one
     write and two reads of the scores, one read and one write of every kept K and V row)."""
-    esz = 2 if str(wl.dtype).endswith("bfloat16") else 4
+    esz = 4 if str(wl.dtype).endswith("float32") else 2
     n_tot = wl.total_prefix_tokens
     k_stream = n_tot * wl.h_kv * wl.d * esz
     sc = n_tot * wl.h_kv * 4
@@ -135,7 +135,7 @@ def bench_decode(args):
     per_kernel, order = traced_pass(adakv, torch, step, trace_steps, kernels_per_step=2)
     assert int(overflow.item()) == 0, "head-room too small for the number of steps"
     kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
-    esz = 2 if str(wl.dtype).endswith("bfloat16") else 4
+    esz = 4 if str(wl.dtype).endswith("float32") else 2
     rows = float(np.mean([int(s[3].sum().item()) for s in sets]))      # rows held at the end
     dom_bytes = rows * wl.d * esz * 2                                   # every K and V row once
     dom_us = max(kernels["decode_attn"], 1e-3)
@@ -170,7 +170,7 @@ def bench_decode(args):
         "value": round(rows / (ms_per_step * 1e-3), 1), "unit": "cached rows/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
+        "dtype": {"torch.bfloat16": "bf16", "torch.float16": "f16"}.get(str(wl.dtype), "f32"), "data": "synthetic",
         "config": {"workload": wl.name + " (decode side)", "h_q": wl.h_q, "h_kv": wl.h_kv, "d": wl.d,
                    "n": wl.n, "w": wl.w, "B": wl.B, "alpha": wl.alpha, "batch": wl.batch,
                    "cached_rows": int(rows), "headroom": hr, "input_sets_rotated": len(sets)},
@@ -314,7 +314,7 @@ def main():
         "value": round(value, 1), "unit": "prefix tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if str(wl.dtype).endswith("bfloat16") else "f32", "data": "synthetic",
+        "dtype": {"torch.bfloat16": "bf16", "torch.float16": "f16"}.get(str(wl.dtype), "f32"), "data": "synthetic",
         "config": {"workload": wl.name, "h_q": wl.h_q, "h_kv": wl.h_kv, "d": wl.d, "n": wl.n,
                    "w": wl.w, "pool_k": wl.pool_k, "B": wl.B, "alpha": wl.alpha, "batch": wl.batch,
                    "input_sets_rotated": len(sets),

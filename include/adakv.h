@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-typedef enum { ADAKV_BF16 = 0, ADAKV_FP32 = 1 } adakv_dtype;
+typedef enum { ADAKV_BF16 = 0, ADAKV_FP32 = 1, ADAKV_FP16 = 2 } adakv_dtype;
 
 typedef enum {
   ADAKV_OK = 0,
@@ -84,11 +84,11 @@ typedef enum {
  * Domain (else ADAKV_EINVAL): h_q % h_kv == 0; w >= 1; pool_k odd >= 1; 0 <= alpha <= 1;
  * 1 <= batch <= ADAKV_MAX_BATCH; n[b] >= 1; w*h_kv <= B[b] <= w*h_kv + h_kv*n[b];
  * tok_off non-decreasing with tok_off[b+1] - tok_off[b] >= n[b] + w.
- * Supported (else ADAKV_EUNSUPPORTED): d in {64, 128}; dtype bf16 or fp32; sum_b h_kv*n[b]
+ * Supported (else ADAKV_EUNSUPPORTED): d in {64, 128}; dtype bf16, fp16 or fp32; sum_b h_kv*n[b]
  * and sum_b B[b] below 2^31.
  */
 typedef struct {
-  int32_t dtype;            /* adakv_dtype of q_window, K, V, K_out, V_out                  */
+  int32_t dtype;            /* adakv_dtype of q_window, K, V, K_out, V_out (and the caches)  */
   int32_t h_q, h_kv, d;     /* query head hq belongs to KV head hq / (h_q / h_kv)           */
   int32_t w, pool_k;
   float alpha;

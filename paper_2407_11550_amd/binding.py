@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "lib", "libadakv.so")
 _lib = None
 
-ADAKV_BF16, ADAKV_FP32 = 0, 1
+ADAKV_BF16, ADAKV_FP32, ADAKV_FP16 = 0, 1, 2
 ADAKV_FLAG_PIPELINE = 2
 ADAKV_FLAG_POOL_THEN_MEAN = 4
 MAX_BATCH = 64
@@ -111,7 +111,7 @@ class Layer:
         self._off = (ctypes.c_int64 * len(self.tok_off))(*self.tok_off)
         ks = k_strides or (h_kv * d, d)
         vs = v_strides or (h_kv * d, d)
-        code = {torch.bfloat16: ADAKV_BF16, torch.float32: ADAKV_FP32}.get(dtype, 99)
+        code = {torch.bfloat16: ADAKV_BF16, torch.float32: ADAKV_FP32, torch.float16: ADAKV_FP16}.get(dtype, 99)
         self.c = _CLayer(code, h_q, h_kv, d, w, pool_k, self.alpha, self.scale, self.batch,
                          self._n, self._B, self._off, ks[0], ks[1], vs[0], vs[1], flags)
 

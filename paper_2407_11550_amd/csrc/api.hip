@@ -40,10 +40,10 @@ static int build_tables(const adakv_layer *L, SeqTab &st, Dims &dm) {
     st.score_off[b] = (int)sc;
     st.out_off[b] = (int)out;
   }
-  if (L->dtype != ADAKV_BF16 && L->dtype != ADAKV_FP32) return ADAKV_EUNSUPPORTED;
+  if (L->dtype != ADAKV_BF16 && L->dtype != ADAKV_FP32 && L->dtype != ADAKV_FP16) return ADAKV_EUNSUPPORTED;
   if (L->d != 64 && L->d != 128) return ADAKV_EUNSUPPORTED;
   if (L->h_kv > 64 || (long long)L->h_q * L->w > (1 << 20)) return ADAKV_EUNSUPPORTED;
-  const long long esz = L->dtype == ADAKV_BF16 ? 2 : 4;
+  const long long esz = L->dtype == ADAKV_FP32 ? 4 : 2;
   const long long strides[4] = {L->k_stride_tok, L->k_stride_head, L->v_stride_tok,
                                 L->v_stride_head};
   for (long long sd : strides) {
@@ -171,7 +171,7 @@ int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const
   TopkCarry tc = {nullptr, 0u, nullptr, nullptr};
   if (pipeline_mode(L, dm)) tc = plan_carry(st, dm, wsp + topk_offset(st, dm, L->dtype));
   hipError_t e = (mfma_path_supported(dm, L->dtype) && !pool_first(L))
-                     ? launch_score_mfma(st, dm, q_window, K, row_lse, scores, wsp, pl, tc, s)
+                     ? launch_score_mfma(st, dm, L->dtype, q_window, K, row_lse, scores, wsp, pl, tc, s)
                      : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
                                             pl, pool_first(L), s);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;

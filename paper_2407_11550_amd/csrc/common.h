@@ -70,9 +70,9 @@ bool mfma_path_supported(const Dims &dm, int dtype);
 hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, const void *q,
                                 const void *K, const float *row_lse, float *scores, char *ws,
                                 const ScorePlan &pl, bool pool_first, hipStream_t s);
-hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
-                             const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-                             const TopkCarry &tc, hipStream_t s);
+hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, int dtype, const void *q,
+                             const void *K, const float *row_lse, float *scores, char *ws,
+                             const ScorePlan &pl, const TopkCarry &tc, hipStream_t s);
 
 // ---- allocation and selection (select.hip) --------------------------------------------------
 // A score becomes a 32-bit key whose unsigned order is the float order (+0.0f turns -0 into +0;

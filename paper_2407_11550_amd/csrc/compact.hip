@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void compact_kernel(
 hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const void *K,
                           const void *V, const int *indices, const int *cu_seqlens, void *K_out,
                           void *V_out, int headroom, int *seg_len, hipStream_t s) {
-  const int esz = dtype == ADAKV_BF16 ? 2 : 4;
+  const int esz = dtype == ADAKV_FP32 ? 4 : 2;
   const int rowb = dm.d * esz;
   const int lpr = rowb / 16;
   const int rows = st.out_off[st.batch];

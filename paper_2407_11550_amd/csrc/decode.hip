@@ -55,6 +55,17 @@ template <> struct Elem<unsigned short> {     // bf16: 8 elements per 16 bytes
     }
   }
 };
+struct f16_t { unsigned short bits; };        // IEEE half: tag type, same size as the bf16 tag
+template <> struct Elem<f16_t> {
+  static constexpr int EPL = 8;
+  static __device__ __forceinline__ void widen(u32x4 v, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = (float)__builtin_bit_cast(_Float16, (unsigned short)(v[i] & 0xFFFFu));
+      f[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(v[i] >> 16));
+    }
+  }
+};
 template <> struct Elem<float> {
   static constexpr int EPL = 4;
   static __device__ __forceinline__ void widen(u32x4 v, float (&f)[4]) {
@@ -474,6 +485,9 @@ hipError_t launch_decode_attn(const SeqTab &st, const Dims &dm, int dtype, int h
   if (dtype == ADAKV_BF16) {
     ok = dm.d == 64 ? run_decode_g<unsigned short, 64>(st, dm, headroom, pl, a, s)
                     : run_decode_g<unsigned short, 128>(st, dm, headroom, pl, a, s);
+  } else if (dtype == ADAKV_FP16) {
+    ok = dm.d == 64 ? run_decode_g<f16_t, 64>(st, dm, headroom, pl, a, s)
+                    : run_decode_g<f16_t, 128>(st, dm, headroom, pl, a, s);
   } else {
     ok = dm.d == 64 ? run_decode_g<float, 64>(st, dm, headroom, pl, a, s)
                     : run_decode_g<float, 128>(st, dm, headroom, pl, a, s);
@@ -485,7 +499,7 @@ hipError_t launch_decode_attn(const SeqTab &st, const Dims &dm, int dtype, int h
 hipError_t launch_append(const SeqTab &st, const Dims &dm, int dtype, int headroom,
                          const void *k_new, const void *v_new, const int *cu, void *Kc, void *Vc,
                          int *seg_len, int *overflow, hipStream_t s) {
-  const int lpr = dm.d * (dtype == ADAKV_BF16 ? 2 : 4) / 16;
+  const int lpr = dm.d * (dtype == ADAKV_FP32 ? 4 : 2) / 16;
   const int nseg = st.batch * dm.h_kv;
   dim3 grid((nseg * lpr + 255) / 256), block(256);
 #define ADAKV_LAUNCH_APPEND(LPR)                                                               \

@@ -38,6 +38,19 @@ template <> struct Elem<bf16_t> {
   }
 };
 
+struct f16_t { unsigned short bits; };
+template <> struct Elem<f16_t> {
+  static constexpr int PER16 = 8;
+  static __device__ __forceinline__ void unpack(const uint4 &v, float *o) {
+    const unsigned a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = (float)__builtin_bit_cast(_Float16, (unsigned short)(a[i] & 0xFFFFu));
+      o[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(a[i] >> 16));
+    }
+  }
+};
+
 template <typename T, int D>
 __device__ __forceinline__ void load_row(const T *p, float *o) {
   constexpr int P = Elem<T>::PER16;
@@ -315,6 +328,9 @@ hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, con
   if (dtype == ADAKV_FP32) {
     if (dm.d == 64) run_generic<float, 64>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
     else run_generic<float, 128>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
+  } else if (dtype == ADAKV_FP16) {
+    if (dm.d == 64) run_generic<f16_t, 64>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
+    else run_generic<f16_t, 128>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
   } else {
     if (dm.d == 64) run_generic<bf16_t, 64>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);
     else run_generic<bf16_t, 128>(st, dm, q, K, row_lse, scores, ws, pl, pool_first, s);

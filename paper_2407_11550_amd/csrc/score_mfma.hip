@@ -50,7 +50,19 @@ constexpr float LN2 = 0.6931471805599453f;
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ bf16x8 as_bf16(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-template <int D, int MB, int RS, int KG, int CHUNK, int PASS>
+// One 32x32x16 product-accumulate on eight 16-bit elements per lane and operand; the fragments are
+// carried as raw 16-byte words (typed bf16x8 above) whatever the element type is.
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+template <bool F16>
+__device__ __forceinline__ floatx16 mfma16(bf16x8 a, bf16x8 b, floatx16 c) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+template <int D, int MB, int RS, int KG, int CHUNK, int PASS, bool F16>
 __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     SeqTab st, ChunkTab ct, Dims dm, float c_log2, const unsigned short *__restrict__ q,
     const unsigned short *__restrict__ K, const float *__restrict__ lse,
@@ -280,8 +292,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
       floatx16 a = {0};
 #pragma unroll
       for (int s = 0; s < KS; ++s)
-        a = PASS == 1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[mb][s], a, 0, 0, 0)
-                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mb][s], kf[s], a, 0, 0, 0);
+        a = PASS == 1 ? mfma16<F16>(kf[s], qf[mb][s], a) : mfma16<F16>(qf[mb][s], kf[s], a);
       acc[mb] = a;
     }
   };
@@ -437,7 +448,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   }
 }
 
-template <int D, int MB, int RS, int KG, int CHUNK>
+template <bool F16, int D, int MB, int RS, int KG, int CHUNK>
 void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
               const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
               const TopkCarry &tc, hipStream_t s) {
@@ -456,7 +467,7 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   const bool fuse_pool = dm.pool_k / 2 <= TILE;
   const float *use_lse = row_lse;
   if (!row_lse) {
-    ADAKV_LAUNCH("score_stats_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 1>), dim3(nblk),
+    ADAKV_LAUNCH("score_stats_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 1, F16>), dim3(nblk),
                  block, s, st, ct, dm, c_log2, (const unsigned short *)q,
                  (const unsigned short *)K, (const float *)nullptr, part_m, part_l,
                  (float *)nullptr, 0, tc);
@@ -467,49 +478,54 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   } else if (tc.zero_begin) {
     launch_topk_clear(tc, s);                 // no statistics sweep to do the clearing
   }
-  ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 2>), dim3(nblk),
+  ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 2, F16>), dim3(nblk),
                block, s, st, ct, dm, c_log2, (const unsigned short *)q, (const unsigned short *)K,
                use_lse, part_m, part_l, fuse_pool ? scores : raw, fuse_pool ? 1 : 0, tc);
   if (!fuse_pool) launch_pool(st, dm, raw, scores, s);
 }
 
-template <int D>
+template <int D, bool F16>
 void run_mfma_d(const SeqTab &st, const Dims &dm, const void *q, const void *K,
                 const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
                 const TopkCarry &tc, hipStream_t s) {
   const int R = dm.g * dm.w;
-  if (R <= 32) run_mfma<D, 1, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  else if (R <= 64) run_mfma<D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  if (R <= 32) run_mfma<F16, D, 1, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  else if (R <= 64) run_mfma<F16, D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
   else if (R <= 128) {
     // chunk length: long chunks amortise the per-workgroup set-up, but every compute unit wants
     // a few workgroups to choose from
     long long keys = 0;
     for (int b = 0; b < st.batch; ++b) keys += st.n[b];
     const long long wg2048 = (keys / 2048 + st.batch) * dm.h_kv;
-    if (wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-    else if (2 * wg2048 >= CHUNK_SWITCH_WGS) run_mfma<D, 2, 2, 2, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-    else run_mfma<D, 2, 2, 2, 512>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    if (wg2048 >= CHUNK_SWITCH_WGS) run_mfma<F16, D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    else if (2 * wg2048 >= CHUNK_SWITCH_WGS) run_mfma<F16, D, 2, 2, 2, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    else run_mfma<F16, D, 2, 2, 2, 512>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
   }
-  else if (R <= 256) run_mfma<D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  else if (R <= 256) run_mfma<F16, D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
   // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
   // a tile half the loads, so four wavefronts of 128 rows
-  else if constexpr (D == 128) run_mfma<D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  else run_mfma<D, 4, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  else if constexpr (D == 128) run_mfma<F16, D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  else run_mfma<F16, D, 4, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
 }
 
 }  // namespace
 
-// bf16 inputs with at most 512 window rows per KV head (g*w); anything else takes the FMA path.
+// 16-bit inputs with at most 512 window rows per KV head (g*w); anything else takes the FMA path.
 bool mfma_path_supported(const Dims &dm, int dtype) {
-  return dtype == ADAKV_BF16 && dm.g * dm.w <= 512 && (dm.d == 64 || dm.d == 128) &&
+  return (dtype == ADAKV_BF16 || dtype == ADAKV_FP16) && dm.g * dm.w <= 512 && (dm.d == 64 || dm.d == 128) &&
          dm.k_stride_tok * 2 < (1ll << 24);   // 24-bit multiplies address a row inside a tile set
 }
 
-hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
-                             const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-                             const TopkCarry &tc, hipStream_t s) {
-  if (dm.d == 64) run_mfma_d<64>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  else run_mfma_d<128>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, int dtype, const void *q,
+                             const void *K, const float *row_lse, float *scores, char *ws,
+                             const ScorePlan &pl, const TopkCarry &tc, hipStream_t s) {
+  if (dtype == ADAKV_FP16) {
+    if (dm.d == 64) run_mfma_d<64, true>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    else run_mfma_d<128, true>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  } else {
+    if (dm.d == 64) run_mfma_d<64, false>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    else run_mfma_d<128, false>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  }
   return hipGetLastError();
 }
 

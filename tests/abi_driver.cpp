@@ -76,7 +76,7 @@ int main(int argc, char **argv) {
     scores_n += (long long)h_kv * n[b];
     rows_out += B[b];
   }
-  const size_t esz = dtype == ADAKV_BF16 ? 2 : 4;
+  const size_t esz = dtype == ADAKV_FP32 ? 4 : 2;
   const int nseg = batch * h_kv;
 
   adakv_layer L;

@@ -64,6 +64,8 @@ DECODE_SHAPES = [
     (2, 1, 128, 1, [50], 0, torch.bfloat16, 2),                # segments of one row
     (4, 4, 128, 8, [1024], 120, torch.bfloat16, 3),            # bf16 without GQA
     (8, 2, 64, 8, [1024], 120, torch.float32, 3),              # fp32 with g 4
+    (32, 8, 128, 32, [3000, 900], 300, torch.float16, 8),      # IEEE half
+    (16, 2, 64, 4, [700], 200, torch.float16, 2),              # half, g 8, d 64
 ]
 
 

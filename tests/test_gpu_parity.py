@@ -54,6 +54,10 @@ SHAPES = [
     (4, 2, 64, 4, 1, 5000, 90, torch.bfloat16),       # the same with d = 64
     (4, 4, 64, 8, 1, 3000, 100, torch.float32),       # no pooling on the fp32 path
     (8, 2, 128, 16, 3, 4500, 200, torch.bfloat16),    # pool radius 1 over several chunks
+    (32, 8, 128, 32, 7, 4099, 250, torch.float16),    # IEEE half on the matrix cores
+    (8, 8, 64, 16, 5, 2777, 100, torch.float16),      # half, d = 64
+    (6, 2, 128, 8, 3, 513, 64, torch.float16),        # half, g = 3
+    (64, 8, 128, 16, 7, 1500, 120, torch.float16),    # half, 128 window rows per head
 ]
 
 
@@ -415,7 +419,7 @@ def test_pool_then_mean_flag_matches_oracle_order(case):
         assert_scores_close(plain.cpu().numpy(), out["scores"].cpu().numpy(), "orders agree without pooling")
 
 
-@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float32], ids=["bf16", "fp32"])
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float32, torch.float16], ids=["bf16", "fp32", "fp16"])
 def test_c_abi_from_a_plain_cpp_program(dt, tmp_path):
     """The library needs neither Python nor PyTorch: tests/abi_driver.bin (hipMalloc, default
     stream) runs the four calls on files and its outputs are checked like the binding's."""
@@ -425,13 +429,13 @@ def test_c_abi_from_a_plain_cpp_program(dt, tmp_path):
     if not os.path.exists(exe):
         pytest.fail("tests/abi_driver.bin is missing: run __graft_entry__.build()")
     _say(f"abi_driver {dt}")
-    wl = synth.small_workload(8, 2, 128 if dt == torch.bfloat16 else 64, 16, 7, [2500, 310], [2 * 150, 2 * 40],
+    wl = synth.small_workload(8, 2, 64 if dt == torch.float32 else 128, 16, 7, [2500, 310], [2 * 150, 2 * 40],
                               dtype=dt, seed=71)
     q, K, V = synth.generate(wl)                                    # on the host
-    raw = (lambda t: t.view(torch.int16).numpy()) if dt == torch.bfloat16 else (lambda t: t.numpy())
+    raw = (lambda t: t.numpy()) if dt == torch.float32 else (lambda t: t.view(torch.int16).numpy())
     for name, t in (("q", q), ("K", K), ("V", V)):
         raw(t.contiguous()).tofile(str(tmp_path / f"{name}.bin"))
-    code = 0 if dt == torch.bfloat16 else 1
+    code = {torch.bfloat16: 0, torch.float32: 1, torch.float16: 2}[dt]
     meta = [code, wl.h_q, wl.h_kv, wl.d, wl.w, wl.pool_k, wl.alpha, 0, wl.batch] + wl.n + wl.B
     (tmp_path / "meta.txt").write_text(" ".join(str(v) for v in meta) + "\n")
     r = subprocess.run([exe, str(tmp_path)], capture_output=True, text=True, timeout=100)
@@ -442,8 +446,8 @@ def test_c_abi_from_a_plain_cpp_program(dt, tmp_path):
                cu_seqlens=torch.from_numpy(np.fromfile(str(tmp_path / "cu_seqlens.bin"), dtype=np.int32)),
                indices=torch.from_numpy(np.fromfile(str(tmp_path / "indices.bin"), dtype=np.int32)))
     for name in ("K_out", "V_out"):
-        if dt == torch.bfloat16:
-            t = torch.from_numpy(np.fromfile(str(tmp_path / f"{name}.bin"), dtype=np.int16)).view(torch.bfloat16)
+        if dt != torch.float32:
+            t = torch.from_numpy(np.fromfile(str(tmp_path / f"{name}.bin"), dtype=np.int16)).view(dt)
         else:
             t = torch.from_numpy(np.fromfile(str(tmp_path / f"{name}.bin"), dtype=np.float32))
         out[name] = t.view(rows, wl.d)

@@ -56,7 +56,7 @@ def test_invalid_layers_are_rejected(lib, kw):
     assert lib.adakv_compact(ctypes.byref(L.c), one, one, one, one, one, one, None) == -1
 
 
-@pytest.mark.parametrize("kw", [dict(d=96), dict(dtype=torch.float16), dict(k_strides=(8 * 128 + 4, 128))])
+@pytest.mark.parametrize("kw", [dict(d=96), dict(dtype=torch.float64), dict(k_strides=(8 * 128 + 4, 128))])
 def test_unsupported_layers(lib, kw):
     L = _layer(**kw)
     one = ctypes.c_void_p(16)
