@@ -179,6 +179,17 @@ int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int3
                   const int32_t *cu_seqlens, void *K_out, void *V_out, void *hip_stream);
 
 /*
+ * The whole step of Algorithm 2 in one call: adakv_score, adakv_allocate, adakv_select and
+ * adakv_compact back to back on `hip_stream`, in pipeline mode (the promise ADAKV_FLAG_PIPELINE
+ * asks for is kept by construction, whatever L->flags says about it).  Arguments and outputs as
+ * for the four calls; every output buffer is required.  Nothing is launched if any check fails.
+ */
+int adakv_compress(const adakv_layer *L, const void *q_window, const void *K, const void *V,
+                   const float *row_lse, float *scores, int32_t *budgets, int32_t *cu_seqlens,
+                   int32_t *indices, void *K_out, void *V_out, void *ws, size_t ws_bytes,
+                   void *hip_stream);
+
+/*
  * ---- Decode side of the flattened layout (Section 3.5; Section 3.1, Eqs. 1-2) --------------
  *
  * After compression every (sequence, KV head) segment s = b*h_kv + c has its own length.  The

@@ -67,6 +67,8 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = args
+    lib.adakv_compress.restype = ctypes.c_int
+    lib.adakv_compress.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, Z, V]
     I = ctypes.c_int32
     for name, args in (("adakv_cache_build", [P, V, V, V, V, I, V, V, V, V]),
                        ("adakv_append", [P, V, V, V, I, V, V, V, V, V]),
@@ -224,22 +226,42 @@ def compact(layer: Layer, K, V, indices, cu_seqlens, K_out=None, V_out=None, str
 
 def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, bufs=None,
              pipeline=True):
-    """The whole step: the four calls back to back on one stream, no host synchronisation.
+    """The whole step on one stream, no host synchronisation: adakv_compress (one ABI call, pipeline
+    mode), or with pipeline=False the four self-contained calls one after the other.
     `bufs` may carry pre-allocated outputs (scores, budgets, cu_seqlens, indices, K_out, V_out)."""
     b = bufs or {}
+    dev = K.device
     if ws is None:
-        ws = torch.empty(max(workspace_bytes(layer), 16), dtype=torch.uint8, device=K.device)
-    # the three calls below keep the promise ADAKV_FLAG_PIPELINE asks for
-    saved = layer.c.flags
-    if pipeline:
-        layer.c.flags = saved | ADAKV_FLAG_PIPELINE
-    try:
+        ws = torch.empty(max(workspace_bytes(layer), 16), dtype=torch.uint8, device=dev)
+    if not pipeline:
         sc = score(layer, q_window, K, row_lse=row_lse, out=b.get("scores"), ws=ws, stream=stream)
         bud, cu = allocate(layer, sc, b.get("budgets"), b.get("cu_seqlens"), ws=ws, stream=stream)
         idx = select(layer, sc, bud, cu, b.get("indices"), ws=ws, stream=stream)
-    finally:
-        layer.c.flags = saved
-    K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
+        K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
+        return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
+    lib = load_library()
+    if not q_window.is_contiguous():
+        raise ValueError("q_window must be contiguous")
+
+    def buf(name, shape, dtype):
+        t = b.get(name)
+        return t if t is not None else torch.empty(shape, dtype=dtype, device=dev)
+
+    sc = buf("scores", layer.num_scores, torch.float32)
+    bud = buf("budgets", layer.num_segments, torch.int32)
+    cu = buf("cu_seqlens", layer.num_segments + 1, torch.int32)
+    idx = buf("indices", layer.num_rows_out, torch.int32)
+    K_out = buf("K_out", (layer.num_rows_out, layer.d), layer.torch_dtype)
+    V_out = buf("V_out", (layer.num_rows_out, layer.d), layer.torch_dtype)
+    st = lib.adakv_compress(ctypes.byref(layer.c), _ptr(q_window, "q_window", layer.torch_dtype),
+                            _ptr(K, "K", layer.torch_dtype), _ptr(V, "V", layer.torch_dtype),
+                            _ptr(row_lse, "row_lse", torch.float32), _ptr(sc, "scores", torch.float32),
+                            _ptr(bud, "budgets", torch.int32), _ptr(cu, "cu_seqlens", torch.int32),
+                            _ptr(idx, "indices", torch.int32), _ptr(K_out, "K_out", layer.torch_dtype),
+                            _ptr(V_out, "V_out", layer.torch_dtype), ctypes.c_void_p(ws.data_ptr()),
+                            ctypes.c_size_t(ws.numel()), _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_compress")
     return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
 
 

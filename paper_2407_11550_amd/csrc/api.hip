@@ -221,6 +221,29 @@ int adakv_compact(const adakv_layer *L, const void *K, const void *V, const int3
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
+int adakv_compress(const adakv_layer *L, const void *q_window, const void *K, const void *V,
+                   const float *row_lse, float *scores, int32_t *budgets, int32_t *cu_seqlens,
+                   int32_t *indices, void *K_out, void *V_out, void *ws, size_t ws_bytes,
+                   void *hip_stream) {
+  // every argument is checked before the first kernel is enqueued
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if (!q_window || !K || !V || !scores || !budgets || !cu_seqlens || !indices || !K_out || !V_out)
+    return ADAKV_EINVAL;
+  if (!aligned16(q_window) || !aligned16(K) || !aligned16(V) || !aligned16(scores) ||
+      !aligned16(K_out) || !aligned16(V_out))
+    return ADAKV_EUNSUPPORTED;
+  if (pool_first(L) && dm.pool_k / 2 > 100) return ADAKV_EUNSUPPORTED;
+  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  adakv_layer P = *L;
+  P.flags |= ADAKV_FLAG_PIPELINE;
+  if ((rc = adakv_score(&P, q_window, K, row_lse, scores, ws, ws_bytes, hip_stream)) != ADAKV_OK) return rc;
+  if ((rc = adakv_allocate(&P, scores, budgets, cu_seqlens, ws, ws_bytes, hip_stream)) != ADAKV_OK) return rc;
+  if ((rc = adakv_select(&P, scores, budgets, cu_seqlens, indices, ws, ws_bytes, hip_stream)) != ADAKV_OK) return rc;
+  return adakv_compact(&P, K, V, indices, cu_seqlens, K_out, V_out, hip_stream);
+}
+
 // ---- decode side ------------------------------------------------------------------------------
 static int check_headroom(const SeqTab &st, const Dims &dm, int32_t headroom) {
   if (headroom < 0) return ADAKV_EINVAL;

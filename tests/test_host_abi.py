@@ -153,3 +153,16 @@ def test_generated_prefill_lse_is_the_prefix_plus_window_normaliser():
         a = O.attention_rows(qd, Kd, wl.n[b], wl.w, norm="prefix+window")
         c = O.attention_rows(qd, Kd, wl.n[b], wl.w, row_lse=lse[b].double().numpy())
         assert np.allclose(a, c, rtol=2e-5, atol=1e-12)
+
+
+def test_compress_checks_everything_before_launching(lib):
+    L = _layer()
+    one = ctypes.c_void_p(16)
+    by = ctypes.byref(L.c)
+    big = 1 << 30
+    assert lib.adakv_compress(by, one, one, one, None, one, one, one, one, one, None, one, big, None) == -1
+    assert lib.adakv_compress(by, one, one, one, None, one, one, one, one, one, one, one, 8, None) == -3
+    assert lib.adakv_compress(by, one, one, one, None, one, one, one, one, one, one, None, big, None) == -3
+    assert lib.adakv_compress(by, one, one, ctypes.c_void_p(24), None, one, one, one, one, one, one, one, big, None) == -2
+    bad = _layer(alpha=2.0)
+    assert lib.adakv_compress(ctypes.byref(bad.c), one, one, one, None, one, one, one, one, one, one, one, big, None) == -1
