@@ -66,6 +66,7 @@ DECODE_SHAPES = [
     (8, 2, 64, 8, [1024], 120, torch.float32, 3),              # fp32 with g 4
     (32, 8, 128, 32, [3000, 900], 300, torch.float16, 8),      # IEEE half
     (16, 2, 64, 4, [700], 200, torch.float16, 2),              # half, g 8, d 64
+    (64, 64, 64, 2, [300, 120], 20, torch.bfloat16, 3),        # 64 KV heads, 128 segments
 ]
 
 

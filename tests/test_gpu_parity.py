@@ -58,6 +58,9 @@ SHAPES = [
     (8, 8, 64, 16, 5, 2777, 100, torch.float16),      # half, d = 64
     (6, 2, 128, 8, 3, 513, 64, torch.float16),        # half, g = 3
     (64, 8, 128, 16, 7, 1500, 120, torch.float16),    # half, 128 window rows per head
+    (16, 16, 64, 4, 7, 900, 30, torch.bfloat16),      # 16 KV heads: two rounds of heads in the finishing kernel
+    (64, 64, 64, 2, 3, 5000, 12, torch.bfloat16),     # the most KV heads the library takes, several chunks
+    (48, 24, 128, 3, 5, 700, 25, torch.float32),      # 24 KV heads on the fp32 path
 ]
 
 
