@@ -283,6 +283,40 @@ def main():
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
 
+    # ---- what a kernel that only reads reaches here: the same K buffers, rotated the same way ---
+    sink = torch.empty(adakv.PROBE_SINK_BYTES, dtype=torch.uint8, device=dev)
+    for i in range(len(sets)):
+        adakv.probe_read(sets[i][1], sink)
+    with adakv.KernelTrace(128) as tr:
+        for i in range(60):
+            adakv.probe_read(sets[i % len(sets)][1], sink)
+    torch.cuda.synchronize()
+    probe_us = float(np.mean([us for _, us in tr.durations_us()]))
+    probe_bytes = sets[0][1].numel() * sets[0][1].element_size()
+    stream_read = {"kernel": "probe_read", "GB/s": round(probe_bytes / (probe_us * 1e-6) / 1e9, 1),
+                   "bytes": probe_bytes, "avg_us": round(probe_us, 2),
+                   "note": "plain 16-byte-per-lane read of the K buffers (window rows included), rotating "
+                           "over the input sets like the step does"}
+    if dominant.startswith("score_"):
+        roofline["frac_of_stream_read"] = round(achieved / stream_read["GB/s"], 4)
+
+    # ---- what the synthetic layer looks like to the Top-k: concentration per head, budgets --------
+    res = step(0)
+    torch.cuda.synchronize()
+    conc, pos = [], 0
+    for b in range(wl.batch):
+        for c in range(wl.h_kv):
+            row = res["scores"][pos:pos + wl.n[b]]
+            top = torch.topk(row, max(1, int(0.05 * wl.n[b]))).values.sum()
+            conc.append(float(top / row.sum()))
+            pos += wl.n[b]
+    bud = res["budgets"].cpu().numpy()
+    stats = {"top5pct_score_mass_per_head": [round(c, 3) for c in conc] if len(conc) <= 16 else
+             {"min": round(min(conc), 3), "median": round(float(np.median(conc)), 3), "max": round(max(conc), 3)},
+             "budgets_min": int(bud.min()), "budgets_max": int(bud.max()),
+             "uniform_share": [(B - wl.w * wl.h_kv) // wl.h_kv for B in wl.B] if wl.batch <= 8 else None,
+             "input_set": 0}
+
     # ---- the oracle on the host cores: whole layers of the same workload, about 10 s ----------
     cpu = None
     if not args.no_cpu_baseline:
@@ -324,6 +358,7 @@ def main():
         "pipeline_algorithmic_bytes": total_alg,
         "score_mfma_tflops": round(flops / (sum(v for k, v in kernels.items() if k.startswith("score_")) * 1e-6) / 1e12, 2),
         "kernels_us": {k: round(kernels[k], 2) for k in order},
+        "stream_read": stream_read, "workload_stats": stats,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

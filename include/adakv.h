@@ -303,6 +303,24 @@ int adakv_trace_arm(void *const *events, int n_events);
 int adakv_trace_disarm(void);
 const char *adakv_trace_name(int i);
 
+/*
+ * Measurement aid for benchmarks (no part of the method): a plain streaming read of a device
+ * buffer, 16 bytes per lane, by ADAKV_PROBE_BLOCKS long-running workgroups.  Its rate on the K
+ * buffers is the figure a scoring sweep, which has to read K once, is compared with.
+ *
+ *   src  (device) bytes bytes, 16-byte aligned, read once; bytes must be a multiple of 16
+ *                 (0 is allowed, src may then be NULL: the sink is all zero afterwards)
+ *   sink (device) ADAKV_PROBE_SINK_BYTES bytes, 16-byte aligned, written: one 16-byte word per
+ *                 wave, the XOR of the words that wave read (the XOR of all of them is the XOR
+ *                 of the buffer's 16-byte words, which is what makes the reads observable)
+ * Returns ADAKV_EINVAL for a NULL sink, a NULL src with bytes > 0 or bytes % 16 != 0,
+ * ADAKV_EUNSUPPORTED for a misaligned pointer, ADAKV_EHIP if the launch failed.  Enqueues one
+ * kernel on hip_stream.
+ */
+#define ADAKV_PROBE_BLOCKS 2048
+#define ADAKV_PROBE_SINK_BYTES (ADAKV_PROBE_BLOCKS * 4 * 16)
+int adakv_probe_read(const void *src, size_t bytes, void *sink, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -88,6 +88,8 @@ def load_library():
     lib.adakv_trace_disarm.argtypes = []
     lib.adakv_trace_name.restype = ctypes.c_char_p
     lib.adakv_trace_name.argtypes = [ctypes.c_int]
+    lib.adakv_probe_read.restype = ctypes.c_int
+    lib.adakv_probe_read.argtypes = [V, Z, V, V]
     _lib = lib
     return lib
 
@@ -272,6 +274,25 @@ def pyramid_budgets(n_layers: int, avg_budget: int, ratio: float):
     if st != 0:
         raise AdaKVError(st, "adakv_pyramid_budgets")
     return [int(v) for v in out]
+
+
+PROBE_SINK_BYTES = 2048 * 4 * 16      # ADAKV_PROBE_SINK_BYTES
+
+
+def probe_read(src, sink=None, stream=None):
+    """adakv_probe_read: one plain streaming read of `src` (a contiguous device tensor whose
+    size in bytes is a multiple of 16); returns the sink, one 16-byte XOR word per wave."""
+    if not src.is_contiguous():
+        raise ValueError("src must be contiguous")
+    if sink is None:
+        sink = torch.empty(PROBE_SINK_BYTES, dtype=torch.uint8, device=src.device)
+    if sink.numel() * sink.element_size() < PROBE_SINK_BYTES:
+        raise ValueError("sink too small")
+    st = load_library().adakv_probe_read(_ptr(src, "src"), ctypes.c_size_t(src.numel() * src.element_size()),
+                                         _ptr(sink, "sink"), _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_probe_read")
+    return sink
 
 
 # ---- decode side of the flattened layout ---------------------------------------------------------

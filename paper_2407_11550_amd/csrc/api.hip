@@ -330,4 +330,14 @@ int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
 
+int adakv_probe_read(const void *src, size_t bytes, void *sink, void *hip_stream) {
+  if ((!src && bytes > 0) || !sink || bytes % 16 != 0) return ADAKV_EINVAL;
+  if (!aligned16(src) || !aligned16(sink)) return ADAKV_EUNSUPPORTED;
+  static_assert(ADAKV_PROBE_SINK_BYTES == ADAKV_PROBE_BLOCKS * 4 * 16, "one word per wave");
+  if (probe_waves_per_block() != 4) return ADAKV_EHIP;
+  hipError_t e = launch_probe_read(src, (long long)(bytes / 16), sink, ADAKV_PROBE_BLOCKS,
+                                   (hipStream_t)hip_stream);
+  return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
 }  // extern "C"

@@ -109,6 +109,10 @@ hipError_t launch_compact(const SeqTab &st, const Dims &dm, int dtype, const voi
                           const void *V, const int *indices, const int *cu_seqlens, void *K_out,
                           void *V_out, int headroom, int *seg_len, hipStream_t s);
 
+// ---- plain streaming read, a measurement aid (probe.hip) -------------------------------------
+hipError_t launch_probe_read(const void *src, long long n16, void *sink, int blocks, hipStream_t s);
+int probe_waves_per_block();
+
 // ---- decode side of the flattened layout (decode.hip) -----------------------------------------
 struct DecodePlan {
   int split;                        // rows of a segment per workgroup

@@ -476,3 +476,22 @@ def test_side_stream_and_unaligned_workspace_give_the_same_result():
     with pytest.raises(adakv.AdaKVError) as e:
         adakv.score(layer, q, K, ws=big[:1000])
     assert e.value.status == -3
+
+
+@pytest.mark.parametrize("nbytes", [0, 16, 16 * 1000, 16 * (2048 * 256 * 4 + 12345), 16 * (5 * 2048 * 256 * 4)])
+def test_streaming_read_probe_reads_every_word_once(nbytes):
+    """The read-rate reference of the benchmark: the XOR of its per-wave words must be the XOR of
+    the buffer's 16-byte words (every word read, none twice), for sizes below one pass of the
+    grid, with a ragged tail, and of several passes."""
+    _say(f"probe_read {nbytes} bytes")
+    rng = np.random.Generator(np.random.PCG64(nbytes % 9973))
+    host = rng.integers(0, 2 ** 32, size=max(nbytes // 4, 4), dtype=np.uint32)
+    src = torch.from_numpy(host.view(np.int32)).to(DEV)[: nbytes // 4]
+    sink = torch.full((adakv.PROBE_SINK_BYTES // 4,), -1, dtype=torch.int32, device=DEV)
+    adakv.probe_read(src, sink)
+    torch.cuda.synchronize()
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32).reshape(-1, 4), axis=0)
+    want = np.bitwise_xor.reduce(host[: nbytes // 4].reshape(-1, 4), axis=0) if nbytes else np.zeros(4, np.uint32)
+    assert np.array_equal(got, want)
+    with pytest.raises(adakv.AdaKVError):
+        adakv.probe_read(torch.zeros(6, dtype=torch.int32, device=DEV), sink)      # 24 bytes

@@ -95,6 +95,16 @@ def test_trace_arm_rejects_bad_arguments(lib):
     assert lib.adakv_trace_disarm() == 0
 
 
+def test_probe_read_rejects_bad_arguments(lib):
+    lib.adakv_probe_read.restype = ctypes.c_int
+    lib.adakv_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.adakv_probe_read(None, 16, 4096, None) == -1
+    assert lib.adakv_probe_read(4096, 16, None, None) == -1
+    assert lib.adakv_probe_read(4096, 24, 8192, None) == -1
+    assert lib.adakv_probe_read(4100, 16, 8192, None) == -2
+    assert lib.adakv_probe_read(4096, 16, 8200, None) == -2
+
+
 def test_generator_is_deterministic_and_shaped():
     from paper_2407_11550_amd import synth
     wl = synth.small_workload(8, 2, 128, 16, 7, [300, 77], [2 * 40, 2 * 20], seed=5)
