@@ -58,7 +58,7 @@ struct TopkCarry;
 
 // ---- scoring (score_generic.hip, score_mfma.hip) ------------------------------------------
 struct ScorePlan {                  // byte offsets into the workspace
-  size_t part_m, part_l;            // [chunks][h_q*w] partial row max / sum of exp
+  size_t part;                      // [chunks][h_q*w] float2: partial row max, sum of exp
   size_t lse;                       // [batch][h_q][w]
   size_t raw;                       // [num_scores] pre-pool scores
   size_t total;
@@ -135,8 +135,8 @@ hipError_t launch_append(const SeqTab &st, const Dims &dm, int dtype, int headro
 // Profiling aid (adakv_trace_arm): while armed on this host thread, every kernel launch carries
 // a pair of the caller's events that receive the kernel's own start and end timestamps.
 bool trace_pair(const char *name, hipEvent_t *start, hipEvent_t *stop);
-void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float *part_m,
-                        const float *part_l, float *lse, hipStream_t s);
+void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float2 *part,
+                        float *lse, hipStream_t s);
 void launch_pool(const SeqTab &st, const Dims &dm, const float *raw, float *scores,
                  hipStream_t s);
 

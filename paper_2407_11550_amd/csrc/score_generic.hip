@@ -87,7 +87,7 @@ __device__ __forceinline__ float logit(const float *qrow, const float *k, float 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void stats_generic_kernel(
     SeqTab st, ChunkTab ct, Dims dm, const T *__restrict__ q, const T *__restrict__ K,
-    float *__restrict__ part_m, float *__restrict__ part_l) {
+    float2 *__restrict__ part) {
   __shared__ float qs[ROW_TILE][D];
   __shared__ float sm[4][ROW_TILE], sl[4][ROW_TILE];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -129,8 +129,7 @@ __global__ __launch_bounds__(256) void stats_generic_kernel(
       for (int i = 0; i < 4; ++i)
         if (sm[i][tid] > -INFINITY) L += sl[i][tid] * expf(sm[i][tid] - M);
       const size_t o = (size_t)blockIdx.x * RQ + (size_t)c * R + r0 + tid;
-      part_m[o] = M;
-      part_l[o] = L;
+      part[o] = make_float2(M, L);
     }
   }
 }
@@ -226,8 +225,7 @@ __global__ __launch_bounds__(256) void pooled_generic_kernel(
 // the lanes stride over the chunks (independent loads), then the 64 partial (max, sum) pairs are
 // merged with shuffles.
 __global__ __launch_bounds__(256) void lse_combine_kernel(SeqTab st, ChunkTab ct, int RQ,
-                                                          const float *__restrict__ part_m,
-                                                          const float *__restrict__ part_l,
+                                                          const float2 *__restrict__ part,
                                                           float *__restrict__ lse) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -235,7 +233,8 @@ __global__ __launch_bounds__(256) void lse_combine_kernel(SeqTab st, ChunkTab ct
   if (row >= RQ) return;
   float M = -INFINITY, L = 0.0f;
   for (int k = ct.off[b] + lane; k < ct.off[b + 1]; k += 64) {
-    const float m = part_m[(size_t)k * RQ + row], l = part_l[(size_t)k * RQ + row];
+    const float2 ml = part[(size_t)k * RQ + row];
+    const float m = ml.x, l = ml.y;
     const float nm = fmaxf(M, m);
     if (nm > -INFINITY) L = L * expf(M - nm) + l * expf(m - nm);
     M = nm;
@@ -274,8 +273,7 @@ ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype) {
   const size_t chunks = make_chunks(st, GEN_CHUNK).off[st.batch];
   const size_t RQ = (size_t)dm.h_q * dm.w;
   size_t o = 0;
-  p.part_m = o; o += align_up(chunks * RQ * 4, 256);
-  p.part_l = o; o += align_up(chunks * RQ * 4, 256);
+  p.part = o; o += align_up(chunks * RQ * 8, 256);
   p.lse = o; o += align_up((size_t)st.batch * RQ * 4, 256);
   p.raw = o; o += align_up((size_t)st.score_off[st.batch] * 4, 256);
   p.total = o;
@@ -283,10 +281,10 @@ ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype) {
   return p;
 }
 
-void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float *part_m,
-                        const float *part_l, float *lse, hipStream_t s) {
+void launch_lse_combine(const SeqTab &st, const ChunkTab &ct, int RQ, const float2 *part,
+                        float *lse, hipStream_t s) {
   ADAKV_LAUNCH("score_lse_combine", lse_combine_kernel, dim3((RQ + 3) / 4, st.batch),
-               dim3(256), s, st, ct, RQ, part_m, part_l, lse);
+               dim3(256), s, st, ct, RQ, part, lse);
 }
 
 void launch_pool(const SeqTab &st, const Dims &dm, const float *raw, float *scores,
@@ -302,13 +300,13 @@ static void run_generic(const SeqTab &st, const Dims &dm, const void *q, const v
                         bool pool_first, hipStream_t s) {
   const ChunkTab ct = make_chunks(st, GEN_CHUNK);
   dim3 grid(ct.off[st.batch], dm.h_kv), block(256);
-  float *part_m = (float *)(ws + pl.part_m), *part_l = (float *)(ws + pl.part_l);
+  float2 *part = (float2 *)(ws + pl.part);
   float *lse = (float *)(ws + pl.lse), *raw = (float *)(ws + pl.raw);
   const float *use_lse = row_lse;
   if (!row_lse) {
     ADAKV_LAUNCH("score_stats_fma", (stats_generic_kernel<T, D>), grid, block, s, st, ct, dm,
-                 (const T *)q, (const T *)K, part_m, part_l);
-    launch_lse_combine(st, ct, dm.h_q * dm.w, part_m, part_l, lse, s);
+                 (const T *)q, (const T *)K, part);
+    launch_lse_combine(st, ct, dm.h_q * dm.w, part, lse, s);
     use_lse = lse;
   }
   if (pool_first) {

@@ -66,7 +66,7 @@ template <int D, int MB, int RS, int KG, int CHUNK, int PASS, bool F16>
 __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     SeqTab st, ChunkTab ct, Dims dm, float c_log2, const unsigned short *__restrict__ q,
     const unsigned short *__restrict__ K, const float *__restrict__ lse,
-    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ out, int halo,
+    float2 *__restrict__ part, float *__restrict__ out, int halo,
     TopkCarry tc) {
   constexpr int NW = RS * KG;                // wavefronts per workgroup
   constexpr int NT = 64 * NW;
@@ -80,7 +80,8 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   __shared__ float sh_rows[2][NW][RW];       // sweep 1: per-wave row (max, sum); sweep 2: [0][0] lse
   constexpr int HALO = TILE;                 // keys scored on either side of the chunk for the pool
   __shared__ float sh_part[PASS == 2 ? RS : 1][PASS == 2 ? CHUNK + 2 * HALO : 1];
-  __shared__ float sh_cm[PASS == 2 ? NT : 1], sh_cl[PASS == 2 ? NT : 1];
+  constexpr int NCOMB = NT > RPAD ? NT : RPAD;   // (thread slices) x (rows) of the statistics combination
+  __shared__ float sh_cm[PASS == 2 ? NCOMB : 1], sh_cl[PASS == 2 ? NCOMB : 1];
   __shared__ unsigned sh_hist[PASS == 2 ? RADIX_BINS : 1];   // first radix digits of the chunk's scores
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -194,12 +195,89 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     for (int i = 0; i < LDPT; ++i) kt[buf][wr_off[i]] = g[i];
   };
 
-  // The first two tile sets are requested before anything else is, so that the query
-  // fragments and the log-sum-exp rows below are fetched in the shadow of that round trip.
+  // Sweep 2 without a caller's log-sum-exp combines sweep 1's partial (max, sum) of this head's
+  // rows over the sequence's chunks.  With at least as many threads as (padded) rows, SL
+  // threads share a row and each takes every SL-th chunk; with fewer, a thread combines RPT
+  // rows one after the other.  CB chunks are loaded at a time, and the first CB of the first
+  // row are requested before anything else: loads return in order, and these come from the
+  // cache while the K rows below come from memory, so the combination runs in the shadow of
+  // the first K round trip instead of after it.
+  constexpr int CB = 32;
+  constexpr int SL = NT >= RPAD ? NT / RPAD : 1;
+  constexpr int RPT = NT >= RPAD ? 1 : RPAD / NT;
+  constexpr int RSTEP = RPAD / RPT;            // rows combined side by side
+  static_assert(SL * RSTEP == NT && RPT * RSTEP == RPAD, "threads and rows must tile each other");
+  const int qi = tid % RSTEP, sl = tid / RSTEP;
+  const int kend = ct.off[b + 1];
+  float2 pml[PASS == 2 ? CB : 1];              // (max, sum) of CB chunks
+  auto load_parts = [&](int k0c, int row) {
+#pragma unroll
+    for (int u = 0; u < CB; ++u) {
+      const int k = min(k0c + u * SL, kend - 1);
+      const size_t o = (size_t)k * RQ + (size_t)c * R + min(row, R - 1);
+      pml[u] = part[o];
+    }
+  };
+  if (PASS == 2 && !lse) load_parts(ct.off[b] + sl, qi);
+
+  // The first two tile sets are requested next; the combination and the loads of the query
+  // fragments (further down, so that they do not hold registers while the partials do) happen
+  // in the shadow of that round trip.
   u32x4 g0[LDPT], g1[LDPT];
   load_set(g0, phys(0));
   load_set(g1, phys(min(1, iters - 1)));
 
+  // sweep 2: log2-domain log-sum-exp of the 16 rows a lane sees in each row block; +inf on the
+  // padding rows makes their weights exactly zero
+  float l2[PASS == 2 ? MB : 1][16];
+  if (PASS == 2) {
+    float *sh_lse = &sh_rows[0][0][0];       // RPAD floats
+    if (lse) {
+      for (int i = tid; i < RPAD; i += NT) sh_lse[i] = (i < R) ? lse[head_row0 + i] * LOG2E : INFINITY;
+    } else {
+      // fold the partials in: first the largest maximum of a batch, then every sum scaled to it
+      // (independent exponentials instead of a chain of rescalings)
+#pragma unroll
+      for (int rr = 0; rr < RPT; ++rr) {
+        const int row = qi + rr * RSTEP;
+        float M = -INFINITY, L = 0.0f;
+        for (int k0c = ct.off[b] + sl; k0c < kend; k0c += CB * SL) {
+          if (rr > 0 || k0c != ct.off[b] + sl) load_parts(k0c, row);
+          float bm = -INFINITY;
+#pragma unroll
+          for (int u = 0; u < CB; ++u)
+            if (k0c + u * SL < kend) bm = fmaxf(bm, pml[u].x * LOG2E);
+          const float nm = fmaxf(M, bm);
+          const float ref = (nm == -INFINITY) ? 0.0f : nm;
+          float acc = L * fast_exp2(M - ref);
+#pragma unroll
+          for (int u = 0; u < CB; ++u)
+            if (k0c + u * SL < kend) acc += pml[u].y * fast_exp2(pml[u].x * LOG2E - ref);
+          L = acc;
+          M = nm;
+        }
+        sh_cm[sl * RPAD + row] = M;
+        sh_cl[sl * RPAD + row] = L;
+      }
+      __syncthreads();
+      for (int row = tid; row < RPAD; row += NT) {
+        float Mt = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < SL; ++i) Mt = fmaxf(Mt, sh_cm[i * RPAD + row]);
+        const float ref = (Mt == -INFINITY) ? 0.0f : Mt;
+        float Lt = 0.0f;
+#pragma unroll
+        for (int i = 0; i < SL; ++i) Lt += sh_cl[i * RPAD + row] * fast_exp2(sh_cm[i * RPAD + row] - ref);
+        sh_lse[row] = (row < R) ? Mt + __builtin_amdgcn_logf(Lt) : INFINITY;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        l2[mb][r] = sh_lse[row0 + mb * 32 + 8 * (r / 4) + 4 * half + (r % 4)];
+  }
   // ---- window queries of this wavefront as MFMA operands, kept for the whole chunk ----------
   // (rows past R are loaded from row R-1 and zeroed, so every load is unconditional)
   bf16x8 qf[MB][KS];
@@ -216,66 +294,6 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     }
   }
 
-  // sweep 2: log2-domain log-sum-exp of the 16 rows a lane sees in each row block; +inf on the
-  // padding rows makes their weights exactly zero
-  float l2[PASS == 2 ? MB : 1][16];
-  if (PASS == 2) {
-    float *sh_lse = &sh_rows[0][0][0];       // RPAD floats
-    if (lse) {
-      for (int i = tid; i < RPAD; i += NT) sh_lse[i] = (i < R) ? lse[head_row0 + i] * LOG2E : INFINITY;
-    } else {
-      // combine sweep 1's partial (max, sum) of this head's rows over the sequence's chunks:
-      // NT/RPAD threads share a row, each takes every (NT/RPAD)-th chunk, LDS joins them
-      constexpr int SL = NT / RPAD;
-      const int qi = tid % RPAD, sl = tid / RPAD;
-      float M = -INFINITY, L = 0.0f;
-      if (qi < R) {
-        // CB chunks' partials are loaded at a time (one round trip: nothing else is live in the
-        // registers yet, and the main loop cannot start before this is done), then folded in
-        constexpr int CB = 32;
-        const int kend = ct.off[b + 1];
-        for (int k0c = ct.off[b] + sl; k0c < kend; k0c += CB * SL) {
-          float pm[CB], pl[CB];
-#pragma unroll
-          for (int u = 0; u < CB; ++u) {
-            const int k = min(k0c + u * SL, kend - 1);
-            const size_t o = (size_t)k * RQ + (size_t)c * R + qi;
-            pm[u] = part_m[o];
-            pl[u] = part_l[o];
-          }
-#pragma unroll
-          for (int u = 0; u < CB; ++u) {
-            if (k0c + u * SL < kend) {
-              const float m = pm[u] * LOG2E;
-              const float nm = fmaxf(M, m);
-              const float ref = (nm == -INFINITY) ? 0.0f : nm;
-              L = L * fast_exp2(M - ref) + pl[u] * fast_exp2(m - ref);
-              M = nm;
-            }
-          }
-        }
-      }
-      sh_cm[tid] = M;
-      sh_cl[tid] = L;
-      __syncthreads();
-      if (tid < RPAD) {
-        float Mt = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < SL; ++i) Mt = fmaxf(Mt, sh_cm[i * RPAD + tid]);
-        const float ref = (Mt == -INFINITY) ? 0.0f : Mt;
-        float Lt = 0.0f;
-#pragma unroll
-        for (int i = 0; i < SL; ++i) Lt += sh_cl[i * RPAD + tid] * fast_exp2(sh_cm[i * RPAD + tid] - ref);
-        sh_lse[tid] = (tid < R) ? Mt + __builtin_amdgcn_logf(Lt) : INFINITY;
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        l2[mb][r] = sh_lse[row0 + mb * 32 + 8 * (r / 4) + 4 * half + (r % 4)];
-  }
   // sweep 1: running statistics of the window row this lane owns in each row block
   float rm[MB], rl[MB];
 #pragma unroll
@@ -407,8 +425,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
         L += sh_rows[1][k * RS + rsi][wi] * fast_exp2(sh_rows[0][k * RS + rsi][wi] - ref);
       if (qi < R) {
         const size_t o = (size_t)cg * RQ + (size_t)c * R + qi;
-        part_m[o] = M * LN2;                       // back to the natural-log domain
-        part_l[o] = L;
+        part[o] = make_float2(M * LN2, L);         // the maximum back in the natural-log domain
       }
     }
   } else {
@@ -455,7 +472,7 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   const ChunkTab ct = make_chunks(st, CHUNK);
   const int nblk = ct.off[st.batch] * dm.h_kv;
   const float c_log2 = dm.scale * LOG2E;
-  float *part_m = (float *)(ws + pl.part_m), *part_l = (float *)(ws + pl.part_l);
+  float2 *part = (float2 *)(ws + pl.part);
   float *lse = (float *)(ws + pl.lse), *raw = (float *)(ws + pl.raw);
   const dim3 block(64 * RS * KG);
   // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a head has so many
@@ -469,10 +486,10 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   if (!row_lse) {
     ADAKV_LAUNCH("score_stats_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 1, F16>), dim3(nblk),
                  block, s, st, ct, dm, c_log2, (const unsigned short *)q,
-                 (const unsigned short *)K, (const float *)nullptr, part_m, part_l,
+                 (const unsigned short *)K, (const float *)nullptr, part,
                  (float *)nullptr, 0, tc);
     if (!fuse_lse) {
-      launch_lse_combine(st, ct, dm.h_q * dm.w, part_m, part_l, lse, s);
+      launch_lse_combine(st, ct, dm.h_q * dm.w, part, lse, s);
       use_lse = lse;
     }
   } else if (tc.zero_begin) {
@@ -480,7 +497,7 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   }
   ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 2, F16>), dim3(nblk),
                block, s, st, ct, dm, c_log2, (const unsigned short *)q, (const unsigned short *)K,
-               use_lse, part_m, part_l, fuse_pool ? scores : raw, fuse_pool ? 1 : 0, tc);
+               use_lse, part, fuse_pool ? scores : raw, fuse_pool ? 1 : 0, tc);
   if (!fuse_pool) launch_pool(st, dm, raw, scores, s);
 }
 

@@ -61,6 +61,9 @@ SHAPES = [
     (16, 16, 64, 4, 7, 900, 30, torch.bfloat16),      # 16 KV heads: two rounds of heads in the finishing kernel
     (64, 64, 64, 2, 3, 5000, 12, torch.bfloat16),     # the most KV heads the library takes, several chunks
     (48, 24, 128, 3, 5, 700, 25, torch.float32),      # 24 KV heads on the fp32 path
+    (16, 2, 64, 64, 7, 2500, 400, torch.bfloat16),    # d = 64 with 512 window rows per head: more rows than threads
+    (10, 2, 64, 64, 5, 1800, 90, torch.float16),      # d = 64, 320 rows (padded to 512)
+    (16, 2, 64, 64, 7, 17500, 300, torch.bfloat16),   # the same with so many chunks that the statistics get their own kernel
 ]
 
 
