@@ -443,12 +443,30 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     __syncthreads();
     float *dst = out + st.score_off[b] + (size_t)c * n;
     const int r = halo ? dm.pool_k / 2 : 0;
-    for (int key = kc0 + tid; key < kc1; key += NT) {
-      const int lo = max(key - r, 0), hi = min(key + r, n - 1);
-      float m = sh_part[0][lo - k0];
-      for (int t = lo + 1; t <= hi; ++t) m = fmaxf(m, sh_part[0][t - k0]);
-      dst[key] = m;
-      if (tc.hist0) atomicAdd(&sh_hist[key_of(m) >> 21], 1u);
+    // A thread pools KPT keys at once, one window offset at a time, so that KPT independent LDS
+    // reads are in flight instead of one chain per key.  Offsets that leave the sequence are
+    // clamped onto its ends (taking an element of the window twice does not change a maximum);
+    // a thread's keys past the chunk end repeat the last key and are not written.
+    constexpr int KPT = CHUNK / NT;
+    static_assert(CHUNK % NT == 0, "every thread pools the same number of keys");
+    float pooled[KPT];
+    int pk[KPT];
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      pk[i] = min(kc0 + tid + i * NT, kc1 - 1);
+      pooled[i] = -INFINITY;
+    }
+    for (int t = -r; t <= r; ++t) {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i)
+        pooled[i] = fmaxf(pooled[i], sh_part[0][min(max(pk[i] + t, 0), n - 1) - k0]);
+    }
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      if (kc0 + tid + i * NT < kc1) {
+        dst[pk[i]] = pooled[i];
+        if (tc.hist0) atomicAdd(&sh_hist[key_of(pooled[i]) >> 21], 1u);
+      }
     }
     if (tc.hist0) {
       __syncthreads();
