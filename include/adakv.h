@@ -304,6 +304,24 @@ int adakv_trace_disarm(void);
 const char *adakv_trace_name(int i);
 
 /*
+ * Diagnostic (host only, launches nothing): which kernels a layer of this shape is scored and
+ * selected with, as one line of "key=value" words, e.g.
+ *   score=mfma dtype=bf16 d=128 rows=128 mb=2 rs=2 kg=2 chunk=2048 stats=sweep lse=fused pool=fused topk=carried
+ * score: mfma (matrix cores) | fma (plain FMA path) | fma-pool-first (ADAKV_FLAG_POOL_THEN_MEAN);
+ * rows = g*w window rows per KV head; mb/rs/kg/chunk: 32-row blocks per wavefront, wavefronts
+ * along rows and along keys, keys per workgroup; stats: sweep (the statistics sweep runs) |
+ * caller (row_lse given); lse / pool: fused into the weights sweep | a kernel of their own;
+ * topk: carried (ADAKV_FLAG_PIPELINE in effect) | separate.  The tests use it to check that
+ * every variant is exercised.
+ *
+ *   have_row_lse  non-zero: describe a call that passes row_lse
+ *   out (host)    out_bytes bytes, written, NUL-terminated
+ * Returns what adakv_score would return for the layer's validity, ADAKV_EINVAL if the text
+ * does not fit.
+ */
+int adakv_describe(const adakv_layer *L, int have_row_lse, char *out, size_t out_bytes);
+
+/*
  * Measurement aid for benchmarks (no part of the method): a plain streaming read of a device
  * buffer, 16 bytes per lane, by ADAKV_PROBE_BLOCKS long-running workgroups.  Its rate on the K
  * buffers is the figure a scoring sweep, which has to read K once, is compared with.

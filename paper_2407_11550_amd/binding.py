@@ -88,6 +88,8 @@ def load_library():
     lib.adakv_trace_disarm.argtypes = []
     lib.adakv_trace_name.restype = ctypes.c_char_p
     lib.adakv_trace_name.argtypes = [ctypes.c_int]
+    lib.adakv_describe.restype = ctypes.c_int
+    lib.adakv_describe.argtypes = [P, ctypes.c_int, ctypes.c_char_p, Z]
     lib.adakv_probe_read.restype = ctypes.c_int
     lib.adakv_probe_read.argtypes = [V, Z, V, V]
     _lib = lib
@@ -274,6 +276,15 @@ def pyramid_budgets(n_layers: int, avg_budget: int, ratio: float):
     if st != 0:
         raise AdaKVError(st, "adakv_pyramid_budgets")
     return [int(v) for v in out]
+
+
+def describe(layer: Layer, row_lse: bool = False) -> dict:
+    """adakv_describe: the kernel variant a layer of this shape gets, as a dict of its words."""
+    buf = ctypes.create_string_buffer(512)
+    st = load_library().adakv_describe(ctypes.byref(layer.c), int(bool(row_lse)), buf, 512)
+    if st != 0:
+        raise AdaKVError(st, "adakv_describe")
+    return dict(word.split("=", 1) for word in buf.value.decode().split())
 
 
 PROBE_SINK_BYTES = 2048 * 4 * 16      # ADAKV_PROBE_SINK_BYTES

@@ -1,6 +1,7 @@
 // C ABI entry points: argument checks, workspace planning, kernel launches.
 // Each call only enqueues work on the caller's stream.
 #include <math.h>
+#include <stdio.h>
 
 #include "common.h"
 
@@ -328,6 +329,31 @@ int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new
                                     K_cache, V_cache, seg_len, overflow, out, lse, wsp,
                                     (hipStream_t)hip_stream);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
+}
+
+int adakv_describe(const adakv_layer *L, int have_row_lse, char *out, size_t out_bytes) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if (!out || out_bytes == 0) return ADAKV_EINVAL;
+  if (pool_first(L) && dm.pool_k / 2 > 100) return ADAKV_EUNSUPPORTED;
+  const char *dt = L->dtype == ADAKV_FP32 ? "fp32" : L->dtype == ADAKV_FP16 ? "fp16" : "bf16";
+  const char *topk = pipeline_mode(L, dm) ? "carried" : "separate";
+  const char *stats = have_row_lse ? "caller" : "sweep";
+  int len;
+  if (mfma_path_supported(dm, L->dtype) && !pool_first(L)) {
+    const MfmaVariant v = choose_mfma_variant(st, dm);
+    len = snprintf(out, out_bytes,
+                   "score=mfma dtype=%s d=%d rows=%d mb=%d rs=%d kg=%d chunk=%d stats=%s lse=%s pool=%s topk=%s",
+                   dt, dm.d, dm.g * dm.w, v.mb, v.rs, v.kg, v.chunk, stats,
+                   have_row_lse ? "caller" : v.fuse_lse ? "fused" : "kernel",
+                   v.fuse_pool ? "fused" : "kernel", topk);
+  } else {
+    len = snprintf(out, out_bytes, "score=%s dtype=%s d=%d rows=%d stats=%s lse=%s pool=kernel topk=%s",
+                   pool_first(L) ? "fma-pool-first" : "fma", dt, dm.d, dm.g * dm.w, stats,
+                   have_row_lse ? "caller" : "kernel", topk);
+  }
+  return (len < 0 || (size_t)len >= out_bytes) ? ADAKV_EINVAL : ADAKV_OK;
 }
 
 int adakv_probe_read(const void *src, size_t bytes, void *sink, void *hip_stream) {

@@ -56,6 +56,15 @@ constexpr int GEN_CHUNK = 256;     // keys per block in the plain-FMA scoring ke
 
 struct TopkCarry;
 
+// Which instantiation of the MFMA scoring kernels a layer gets (score_mfma.hip).
+struct MfmaVariant {
+  int mb, rs, kg;      // 32-row blocks per wavefront; wavefronts along window rows, along keys
+  int chunk;           // keys per workgroup
+  bool fuse_lse;       // sweep 2 combines sweep 1's partial statistics itself
+  bool fuse_pool;      // sweep 2 applies the max-pool itself
+};
+MfmaVariant choose_mfma_variant(const SeqTab &st, const Dims &dm);
+
 // ---- scoring (score_generic.hip, score_mfma.hip) ------------------------------------------
 struct ScorePlan {                  // byte offsets into the workspace
   size_t part;                      // [chunks][h_q*w] float2: partial row max, sum of exp

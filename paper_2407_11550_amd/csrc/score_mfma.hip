@@ -125,8 +125,11 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // An iteration covers KG consecutive tiles (one per wavefront group).  All threads of the
   // workgroup load the iteration's rows together: 16 lanes per 256-byte row, every byte read
   // once per workgroup, addressed as a wave-uniform 64-bit base (scalar registers) plus a
-  // 32-bit per-lane offset.  The loads of iterations it+1 and it+2 are in flight while
-  // iteration it is computed (two register sets, two LDS buffers, one barrier per iteration).
+  // 32-bit per-lane offset.  The loads of iterations it+1 .. it+DEPTH are in flight while
+  // iteration it is computed (DEPTH register sets, two LDS buffers, one barrier per iteration).
+  // register sets = iterations of loads in flight (a third set fits the statistics sweep's
+  // registers and was measured: no faster)
+  constexpr int DEPTH = 2;
   constexpr int TW = TILE * ROW16;                     // 16-byte words per tile
   constexpr int LDPT = KG * TW / NT;                   // loads per thread per iteration
   static_assert(KG * TW % NT == 0 && LDPT >= 1, "tile set must split evenly over the threads");
@@ -223,9 +226,9 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // The first two tile sets are requested next; the combination and the loads of the query
   // fragments (further down, so that they do not hold registers while the partials do) happen
   // in the shadow of that round trip.
-  u32x4 g0[LDPT], g1[LDPT];
-  load_set(g0, phys(0));
-  load_set(g1, phys(min(1, iters - 1)));
+  u32x4 g[DEPTH][LDPT];
+#pragma unroll
+  for (int j = 0; j < DEPTH; ++j) load_set(g[j], phys(min(j, iters - 1)));
 
   // sweep 2: log2-domain log-sum-exp of the 16 rows a lane sees in each row block; +inf on the
   // padding rows makes their weights exactly zero
@@ -356,7 +359,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   int prev_tile = -1;                                  // -1: none pending
 
   // iteration it: LDS buffer it%2 holds its tiles; register set gb is in flight with the loads of
-  // it+1; set ga is free and takes it+2's
+  // it+1; set ga is free and takes it+DEPTH's
   auto step = [&](int it, u32x4 (&ga)[LDPT], u32x4 (&gb)[LDPT]) {
     bf16x8 kf[KS];
     const u32x4 *buf = kt[it & 1];
@@ -364,7 +367,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     for (int s = 0; s < KS; ++s) kf[s] = as_bf16(buf[rd_off + s * 2]);
     // always issued (the last iterations re-read the final set): a conditional load would make
     // the compiler wait for every outstanding load before the stores below
-    load_set(ga, phys(min(it + 2, iters - 1)));
+    load_set(ga, phys(min(it + DEPTH, iters - 1)));
     const int tile = phys(it) * KG + kg;
     const bool have = tile < ntiles;
     if (have && prev_tile >= 0 && is_full(prev_tile)) {
@@ -390,11 +393,12 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     __syncthreads();
   };
   {
-    store_set(g0, 0);
+    store_set(g[0], 0);
     __syncthreads();
-    for (int it = 0; it < iters; it += 2) {
-      step(it, g0, g1);
-      if (it + 1 < iters) step(it + 1, g1, g0);
+    for (int it = 0; it < iters; it += DEPTH) {
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j)
+        if (it + j < iters) step(it + j, g[j], g[(j + 1) % DEPTH]);
     }
     if (prev_tile >= 0) {
       if (is_full(prev_tile)) epilogue(std::false_type{}, accp, prev_tile);
@@ -484,7 +488,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
 }
 
 template <bool F16, int D, int MB, int RS, int KG, int CHUNK>
-void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
+void run_mfma(const MfmaVariant &v, const SeqTab &st, const Dims &dm, const void *q, const void *K,
               const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
               const TopkCarry &tc, hipStream_t s) {
   const ChunkTab ct = make_chunks(st, CHUNK);
@@ -493,13 +497,7 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
   float2 *part = (float2 *)(ws + pl.part);
   float *lse = (float *)(ws + pl.lse), *raw = (float *)(ws + pl.raw);
   const dim3 block(64 * RS * KG);
-  // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a head has so many
-  // (chunks x rows) that every workgroup re-reading them would cost more than a kernel, and it
-  // applies the max-pool itself when the pool radius fits into the one-tile halo.
-  int max_chunks = 0;
-  for (int b = 0; b < st.batch; ++b) max_chunks = ct.off[b + 1] - ct.off[b] > max_chunks ? ct.off[b + 1] - ct.off[b] : max_chunks;
-  const bool fuse_lse = (long long)max_chunks * dm.g * dm.w <= 8192;
-  const bool fuse_pool = dm.pool_k / 2 <= TILE;
+  const bool fuse_lse = v.fuse_lse, fuse_pool = v.fuse_pool;
   const float *use_lse = row_lse;
   if (!row_lse) {
     ADAKV_LAUNCH("score_stats_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 1, F16>), dim3(nblk),
@@ -520,27 +518,24 @@ void run_mfma(const SeqTab &st, const Dims &dm, const void *q, const void *K,
 }
 
 template <int D, bool F16>
-void run_mfma_d(const SeqTab &st, const Dims &dm, const void *q, const void *K,
-                const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-                const TopkCarry &tc, hipStream_t s) {
-  const int R = dm.g * dm.w;
-  if (R <= 32) run_mfma<F16, D, 1, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  else if (R <= 64) run_mfma<F16, D, 2, 1, 4, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  else if (R <= 128) {
-    // chunk length: long chunks amortise the per-workgroup set-up, but every compute unit wants
-    // a few workgroups to choose from
-    long long keys = 0;
-    for (int b = 0; b < st.batch; ++b) keys += st.n[b];
-    const long long wg2048 = (keys / 2048 + st.batch) * dm.h_kv;
-    if (wg2048 >= CHUNK_SWITCH_WGS) run_mfma<F16, D, 2, 2, 2, 2048>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-    else if (2 * wg2048 >= CHUNK_SWITCH_WGS) run_mfma<F16, D, 2, 2, 2, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-    else run_mfma<F16, D, 2, 2, 2, 512>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+hipError_t run_mfma_d(const MfmaVariant &v, const SeqTab &st, const Dims &dm, const void *q,
+                      const void *K, const float *row_lse, float *scores, char *ws,
+                      const ScorePlan &pl, const TopkCarry &tc, hipStream_t s) {
+#define ADAKV_MFMA_CASE(MB, RS, KG, CHUNK)                                                      \
+  if (v.mb == MB && v.rs == RS && v.kg == KG && v.chunk == CHUNK) {                             \
+    run_mfma<F16, D, MB, RS, KG, CHUNK>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s);       \
+    return hipGetLastError();                                                                   \
   }
-  else if (R <= 256) run_mfma<F16, D, 2, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
-  // a tile half the loads, so four wavefronts of 128 rows
-  else if constexpr (D == 128) run_mfma<F16, D, 2, 8, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  else run_mfma<F16, D, 4, 4, 1, 1024>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  ADAKV_MFMA_CASE(1, 1, 4, 2048)
+  ADAKV_MFMA_CASE(2, 1, 4, 2048)
+  ADAKV_MFMA_CASE(2, 2, 2, 2048)
+  ADAKV_MFMA_CASE(2, 2, 2, 1024)
+  ADAKV_MFMA_CASE(2, 2, 2, 512)
+  ADAKV_MFMA_CASE(2, 4, 1, 1024)
+  if constexpr (D == 128) { ADAKV_MFMA_CASE(2, 8, 1, 1024) }
+  else { ADAKV_MFMA_CASE(4, 4, 1, 1024) }
+#undef ADAKV_MFMA_CASE
+  return hipErrorInvalidValue;                 // a variant nobody instantiated
 }
 
 }  // namespace
@@ -551,17 +546,48 @@ bool mfma_path_supported(const Dims &dm, int dtype) {
          dm.k_stride_tok * 2 < (1ll << 24);   // 24-bit multiplies address a row inside a tile set
 }
 
+// The one place that decides which instantiation scores a layer: rows per wavefront and the
+// split of a workgroup's wavefronts over window rows (RS) and keys (KG) follow the number of
+// window rows per KV head; the chunk length follows the number of workgroups.
+MfmaVariant choose_mfma_variant(const SeqTab &st, const Dims &dm) {
+  MfmaVariant v;
+  const int R = dm.g * dm.w;
+  if (R <= 32) v = {1, 1, 4, 2048, false, false};
+  else if (R <= 64) v = {2, 1, 4, 2048, false, false};
+  else if (R <= 128) {
+    // chunk length: long chunks amortise the per-workgroup set-up, but every compute unit wants
+    // a few workgroups to choose from
+    long long keys = 0;
+    for (int b = 0; b < st.batch; ++b) keys += st.n[b];
+    const long long wg2048 = (keys / 2048 + st.batch) * dm.h_kv;
+    const int chunk = wg2048 >= CHUNK_SWITCH_WGS ? 2048 : 2 * wg2048 >= CHUNK_SWITCH_WGS ? 1024 : 512;
+    v = {2, 2, 2, chunk, false, false};
+  } else if (R <= 256) v = {2, 4, 1, 1024, false, false};
+  // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
+  // a tile half the loads, so four wavefronts of 128 rows
+  else if (dm.d == 128) v = {2, 8, 1, 1024, false, false};
+  else v = {4, 4, 1, 1024, false, false};
+  // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a head has so many
+  // (chunks x rows) that every workgroup re-reading them would cost more than a kernel, and it
+  // applies the max-pool itself when the pool radius fits into the one-tile halo.
+  const ChunkTab ct = make_chunks(st, v.chunk);
+  int max_chunks = 0;
+  for (int b = 0; b < st.batch; ++b)
+    max_chunks = ct.off[b + 1] - ct.off[b] > max_chunks ? ct.off[b + 1] - ct.off[b] : max_chunks;
+  v.fuse_lse = (long long)max_chunks * R <= 8192;
+  v.fuse_pool = dm.pool_k / 2 <= TILE;
+  return v;
+}
+
 hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, int dtype, const void *q,
                              const void *K, const float *row_lse, float *scores, char *ws,
                              const ScorePlan &pl, const TopkCarry &tc, hipStream_t s) {
-  if (dtype == ADAKV_FP16) {
-    if (dm.d == 64) run_mfma_d<64, true>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-    else run_mfma_d<128, true>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  } else {
-    if (dm.d == 64) run_mfma_d<64, false>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-    else run_mfma_d<128, false>(st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  }
-  return hipGetLastError();
+  const MfmaVariant v = choose_mfma_variant(st, dm);
+  if (dtype == ADAKV_FP16)
+    return dm.d == 64 ? run_mfma_d<64, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s)
+                      : run_mfma_d<128, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+  return dm.d == 64 ? run_mfma_d<64, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s)
+                    : run_mfma_d<128, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s);
 }
 
 }  // namespace adakv

@@ -77,6 +77,43 @@ def test_whole_step_matches_oracle(shape):
     _check_all(wl, q, K, V, out)
 
 
+def variant_shapes():
+    """One shape per instantiation of the MFMA scoring kernels (both 16-bit types, both head
+    dimensions, every rows-per-head class and chunk length), plus the two forms that are not
+    fused (the statistics combined and the pool applied by kernels of their own).  Same tuple
+    layout as SHAPES.  tests/test_variant_coverage.py checks on the CPU that the list does
+    reach every variant."""
+    out = []
+    for dt in (torch.bfloat16, torch.float16):
+        for d in (64, 128):
+            out += [
+                (4, 2, d, 8, 7, 700, 60, dt),            # 16 rows per head
+                (4, 2, d, 24, 5, 900, 70, dt),           # 48 rows
+                (8, 2, d, 32, 7, 3000, 150, dt),         # 128 rows, few workgroups: 512-key chunks
+                (64, 64, d, 100, 7, 7000, 130, dt),      # 100 rows, 64 heads: 1024-key chunks
+                (64, 64, d, 100, 3, 15000, 120, dt),     # enough workgroups for 2048-key chunks
+                (4, 2, d, 100, 7, 2500, 200, dt),        # 200 rows
+                (8, 2, d, 96, 9, 2100, 180, dt),         # 384 rows (padded to 512)
+            ]
+    out += [
+        (8, 2, 128, 32, 71, 3000, 150, torch.bfloat16),   # pool radius beyond the fused halo
+        (8, 2, 64, 32, 67, 2600, 150, torch.float16),
+        (16, 2, 128, 64, 7, 17500, 300, torch.float16),   # 512 rows x 18 chunks: statistics kernel
+    ]
+    return out
+
+
+@pytest.mark.parametrize("shape", variant_shapes(), ids=lambda s: "hq%d_h%d_d%d_w%d_k%d_n%d_B%d_%s" % (s[:7] + (str(s[7])[6:],)))
+def test_every_scoring_variant_matches_oracle(shape):
+    h_q, h, d, w, k, n, Bh, dt = shape
+    _say(f"variant {shape}")
+    wl = synth.small_workload(h_q, h, d, w, k, n, h * Bh, dtype=dt, seed=13)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer, out = _run(wl, q, K, V)
+    _say("  " + " ".join(f"{k_}={v}" for k_, v in adakv.describe(layer).items()))
+    _check_all(wl, q, K, V, out)
+
+
 def test_tiny_config():
     _say("tiny config")
     wl = synth.workload("tiny")

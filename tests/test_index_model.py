@@ -43,3 +43,33 @@ def test_row_clamp_stays_inside_the_needed_rows(chunk_len, kg):
         for pool_r in [0, 1, 3, 16, 32]:
             for halo, sweep in [(1, 2), (0, 2), (0, 1)]:
                 assert violations(n, chunk_len, kg, pool_r, halo, sweep) == 0, (n, pool_r, halo, sweep)
+
+
+def pool_violations(n, chunk_len, nt, pool_r, halo):
+    """The fused max-pool of sweep 2: thread tid pools keys kc0 + tid + i*nt (clamped to the
+    chunk's last key) and reads offsets -r..r around them, clamped to the sequence, from the
+    chunk's score array that starts at key k0 and holds span = k1 - k0 entries."""
+    bad = 0
+    r = pool_r if halo else 0
+    for chunk in range((n + chunk_len - 1) // chunk_len):
+        kc0 = chunk * chunk_len
+        kc1 = min(n, kc0 + chunk_len)
+        k0 = kc0 - HALO if (halo and kc0 > 0) else kc0
+        k1 = min(n, kc1 + r) if halo else kc1
+        span = k1 - k0
+        bad += span > chunk_len + 2 * HALO
+        for tid in (0, 1, nt // 2, nt - 1):
+            for i in range(chunk_len // nt):
+                pk = min(kc0 + tid + i * nt, kc1 - 1)
+                for t in range(-r, r + 1):
+                    idx = min(max(pk + t, 0), n - 1) - k0
+                    bad += not (0 <= idx < span)
+    return bad
+
+
+@pytest.mark.parametrize("chunk_len,nt", [(512, 256), (1024, 256), (2048, 256), (1024, 512)])
+def test_fused_pool_reads_stay_inside_the_chunk_array(chunk_len, nt):
+    for n in [1, 5, 31, 33, 300, 511, 513, 2047, 2049, 2080, 4096, 4099, 6145]:
+        for pool_r in [0, 1, 3, 16, 32]:
+            for halo in (0, 1):
+                assert pool_violations(n, chunk_len, nt, pool_r, halo) == 0, (n, pool_r, halo)

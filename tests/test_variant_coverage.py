@@ -1,0 +1,61 @@
+"""CPU-side check that the GPU parity shapes reach every instantiation of the scoring kernels.
+
+adakv_describe reports, on the host, which variant a layer shape is scored with; the shapes are
+the ones the GPU tests run (imported from them, nothing is launched here)."""
+import itertools
+
+import torch
+
+import paper_2407_11550_amd as adakv
+from paper_2407_11550_amd import synth
+
+import test_gpu_parity as G
+
+
+def _variants_reached():
+    seen = set()
+    shapes = list(G.SHAPES) + list(G.variant_shapes())
+    layers = [synth.small_workload(h_q, h, d, w, k, n, h * Bh, dtype=dt) for h_q, h, d, w, k, n, Bh, dt in shapes]
+    layers += [synth.small_workload(h_q, h, d, w, k, n, B, alpha=a, dtype=dt) for h_q, h, d, w, k, n, B, a, dt, _ in G._fuzz_shapes()]
+    layers += [synth.workload(nm) for nm in ("tiny", "llama8b_32k", "llama8b_128k", "llama8b_ragged", "llama70b_128k")]
+    for wl in layers:
+        v = adakv.describe(adakv.Layer.from_workload(wl))
+        if v["score"] == "mfma":
+            seen.add((v["dtype"], int(v["d"]), int(v["mb"]), int(v["rs"]), int(v["kg"]), int(v["chunk"])))
+            seen.add(("lse", v["lse"], int(v["d"])))
+            seen.add(("pool", v["pool"], int(v["d"])))
+        else:
+            seen.add((v["score"], v["dtype"], int(v["d"])))
+    return seen
+
+
+def test_gpu_shapes_reach_every_scoring_variant(lib):
+    seen = _variants_reached()
+    want = set()
+    for dt, d in itertools.product(("bf16", "fp16"), (64, 128)):
+        for mb, rs, kg, chunk in ((1, 1, 4, 2048), (2, 1, 4, 2048), (2, 2, 2, 512), (2, 2, 2, 1024),
+                                  (2, 2, 2, 2048), (2, 4, 1, 1024)):
+            want.add((dt, d, mb, rs, kg, chunk))
+        want.add((dt, d, 2, 8, 1, 1024) if d == 128 else (dt, d, 4, 4, 1, 1024))
+    for d in (64, 128):
+        want |= {("lse", "fused", d), ("lse", "kernel", d), ("pool", "fused", d), ("pool", "kernel", d)}
+    want |= {("fma", "fp32", 64), ("fma", "fp32", 128)}
+    missing = sorted(map(str, want - seen))
+    assert not missing, "no GPU parity shape reaches: " + ", ".join(missing)
+
+
+def test_describe_follows_flags_and_rejects_what_score_rejects(lib):
+    wl = synth.workload("llama8b_128k")
+    plain = adakv.describe(adakv.Layer.from_workload(wl))
+    assert plain["score"] == "mfma" and plain["chunk"] == "2048" and plain["topk"] == "separate"
+    assert adakv.describe(adakv.Layer.from_workload(wl, flags=adakv.binding.ADAKV_FLAG_PIPELINE))["topk"] == "carried"
+    assert adakv.describe(adakv.Layer.from_workload(wl), row_lse=True)["stats"] == "caller"
+    first = adakv.describe(adakv.Layer.from_workload(wl, flags=adakv.binding.ADAKV_FLAG_POOL_THEN_MEAN))
+    assert first["score"] == "fma-pool-first"
+    wl.pool_k = 4
+    try:
+        adakv.describe(adakv.Layer.from_workload(wl))
+    except adakv.AdaKVError as e:
+        assert e.status == -1
+    else:
+        raise AssertionError("an even pool kernel must be rejected")
