@@ -171,6 +171,8 @@ def skewed_budgets(wl: Workload, seed: int = 0, skew: float = 1.5):
     out = []
     for nb, Bb in zip(wl.n, wl.B):
         Bp = Bb - wl.w * wl.h_kv
+        if not 0 <= Bp <= nb * wl.h_kv:
+            raise ValueError(f"budget {Bb} does not fit {wl.h_kv} heads of {nb} prefix tokens plus the window")
         wgt = np.exp(skew * rng.standard_normal(wl.h_kv))
         raw = np.minimum(np.floor(Bp * wgt / wgt.sum()).astype(np.int64), nb)
         left = Bp - int(raw.sum())

@@ -302,11 +302,9 @@ def test_eviction_loss_adaptive_against_uniform_allocation():
     assert sum(a < u for a, u in zip(losses[0.2], losses[1.0])) >= 5      # on most samples
 
 
-def test_seeded_decode_shape_sweep_matches_oracle():
-    """Twenty-four seeded shapes: group sizes 1 to 8, both head dimensions and dtypes, one to five
-    sequences, head-room 0 to 40, segments from the window alone to thousands of rows; two fused
-    steps each (the second works on the lengths the first one published)."""
+def decode_sweep_shapes():
     rng = np.random.default_rng(77)
+    shapes = []
     for i in range(24):
         g = int(rng.choice([1, 2, 4, 8]))
         h = int(rng.choice([1, 2, 4, 8]))
@@ -318,22 +316,54 @@ def test_seeded_decode_shape_sweep_matches_oracle():
         n = [int(rng.integers(2, top + 1)) for _ in range(batch)]
         per_head = int(rng.integers(0, min(n) + 1))
         hr = int(rng.choice([0, 1, 2, 40]))
-        shape = (g * h, h, d, w, n, per_head, dt, hr)
+        shapes.append(((g * h, h, d, w, n, per_head, dt, hr), 300 + i, float(rng.choice([0.0, 1.0, 2.5]))))
+    return shapes
+
+
+def _two_fused_steps(shape, seed, skew):
+    h_q, h, d, w, n, per_head, dt, hr = shape
+    wl, layer, Kc, Vc, cu, seg_len = _decode_case(h_q, h, d, w, n, per_head, dt, hr, seed=seed, skew=skew)
+    qn, kn, vn = synth.decode_inputs(wl, 2, seed=seed, device=DEV)
+    oK, oV, olen = to_f64(Kc), to_f64(Vc), seg_len.cpu().numpy().astype(np.int64)
+    cuh = cu.cpu().numpy()
+    overflow = torch.zeros(1, dtype=torch.int32, device=DEV)
+    vmax = float(Vc.float().abs().max()) + 1.0
+    full = False
+    for t in range(2):
+        out, lse = adakv.decode_step(layer, qn[t], kn[t], vn[t], cu, hr, Kc, Vc, seg_len, overflow=overflow,
+                                     want_lse=True)
+        torch.cuda.synchronize()
+        full |= D.append(oK, oV, cuh, hr, olen, to_f64(kn[t]).reshape(-1, wl.d), to_f64(vn[t]).reshape(-1, wl.d))
+        assert np.array_equal(seg_len.cpu().numpy(), olen), (shape, t)
+        assert bool(overflow.item()) == full, (shape, t)
+        ref_out, ref_lse = D.decode_attention(to_f64(qn[t]), oK, oV, cuh, hr, olen, wl.g)
+        _assert_decode_close(out, lse, ref_out, ref_lse, vmax, f"{shape} step {t}")
+
+
+def test_seeded_decode_shape_sweep_matches_oracle():
+    """Twenty-four seeded shapes: group sizes 1 to 8, both head dimensions and dtypes, one to five
+    sequences, head-room 0 to 40, segments from the window alone to thousands of rows; two fused
+    steps each (the second works on the lengths the first one published)."""
+    for shape, seed, skew in decode_sweep_shapes():
         _say(f"decode sweep {shape}")
-        wl, layer, Kc, Vc, cu, seg_len = _decode_case(g * h, h, d, w, n, per_head, dt, hr, seed=300 + i,
-                                                      skew=float(rng.choice([0.0, 1.0, 2.5])))
-        qn, kn, vn = synth.decode_inputs(wl, 2, seed=300 + i, device=DEV)
-        oK, oV, olen = to_f64(Kc), to_f64(Vc), seg_len.cpu().numpy().astype(np.int64)
-        cuh = cu.cpu().numpy()
-        overflow = torch.zeros(1, dtype=torch.int32, device=DEV)
-        vmax = float(Vc.float().abs().max()) + 1.0
-        full = False
-        for t in range(2):
-            out, lse = adakv.decode_step(layer, qn[t], kn[t], vn[t], cu, hr, Kc, Vc, seg_len, overflow=overflow,
-                                         want_lse=True)
-            torch.cuda.synchronize()
-            full |= D.append(oK, oV, cuh, hr, olen, to_f64(kn[t]).reshape(-1, wl.d), to_f64(vn[t]).reshape(-1, wl.d))
-            assert np.array_equal(seg_len.cpu().numpy(), olen), (shape, t)
-            assert bool(overflow.item()) == full, (shape, t)
-            ref_out, ref_lse = D.decode_attention(to_f64(qn[t]), oK, oV, cuh, hr, olen, wl.g)
-            _assert_decode_close(out, lse, ref_out, ref_lse, vmax, f"{shape} step {t}")
+        _two_fused_steps(shape, seed, skew)
+
+
+# The element type x head dimension x group size combinations (one kernel instantiation each)
+# that neither DECODE_SHAPES nor the seeded sweep reaches; tests/test_variant_coverage.py checks
+# that the three lists together reach all 24.
+DECODE_VARIANT_SHAPES = [
+    (4, 4, 64, 4, [500, 90], 70, torch.float16, 2),
+    (4, 2, 64, 4, [800], 150, torch.float16, 1),
+    (8, 2, 64, 8, [1200], 200, torch.float16, 0),
+    (2, 2, 128, 4, [600, 170], 90, torch.float16, 3),
+    (4, 2, 128, 2, [900], 120, torch.float16, 2),
+    (16, 2, 128, 4, [2500], 700, torch.float16, 4),
+    (8, 2, 128, 8, [1500, 200], 150, torch.float32, 2),
+]
+
+
+@pytest.mark.parametrize("shape", DECODE_VARIANT_SHAPES, ids=lambda s: "hq%d_h%d_d%d_%s" % (s[0], s[1], s[2], str(s[6])[6:]))
+def test_every_decode_variant_matches_oracle(shape):
+    _say(f"decode variant {shape}")
+    _two_fused_steps(shape, seed=55, skew=1.5)

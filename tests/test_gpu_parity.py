@@ -96,6 +96,10 @@ def variant_shapes():
                 (8, 2, d, 96, 9, 2100, 180, dt),         # 384 rows (padded to 512)
             ]
     out += [
+        (18, 2, 128, 64, 7, 1500, 100, torch.bfloat16),   # 576 rows per head: beyond the matrix-core
+        (18, 2, 64, 64, 5, 900, 80, torch.float16),       # kernels, the plain-FMA path on 16-bit inputs
+        (18, 2, 64, 64, 5, 700, 80, torch.bfloat16),
+        (18, 2, 128, 64, 3, 800, 90, torch.float16),
         (8, 2, 128, 32, 71, 3000, 150, torch.bfloat16),   # pool radius beyond the fused halo
         (8, 2, 64, 32, 67, 2600, 150, torch.float16),
         (16, 2, 128, 64, 7, 17500, 300, torch.float16),   # 512 rows x 18 chunks: statistics kernel
@@ -424,13 +428,19 @@ def test_whole_step_replays_from_a_hip_graph():
             assert torch.equal(eager[key], bufs[key]), (i, key)
 
 
-@pytest.mark.parametrize("case", [
+POOL_FIRST_CASES = [
     (8, 2, 128, 8, 7, [3000, 41], torch.bfloat16, False),
     (4, 4, 64, 8, 5, [1024], torch.float32, False),
     (6, 2, 128, 5, 15, [700, 9, 260], torch.bfloat16, True),
     (8, 8, 64, 2, 1, [500], torch.bfloat16, False),
     (2, 1, 128, 3, 201, [333], torch.float32, False),      # the largest pool radius this order takes
-], ids=["bf16", "fp32", "row_lse", "no_pool", "radius100"])
+    (8, 2, 128, 8, 7, [900], torch.float16, False),
+    (4, 2, 64, 16, 3, [1300, 70], torch.float16, False),
+]
+
+
+@pytest.mark.parametrize("case", POOL_FIRST_CASES,
+                         ids=["bf16", "fp32", "row_lse", "no_pool", "radius100", "fp16", "fp16_d64"])
 def test_pool_then_mean_flag_matches_oracle_order(case):
     """ADAKV_FLAG_POOL_THEN_MEAN: scores follow the oracle's order="pool_then_mean"; the later
     steps are exact functions of the scores as always."""

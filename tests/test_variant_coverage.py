@@ -9,6 +9,7 @@ import torch
 import paper_2407_11550_amd as adakv
 from paper_2407_11550_amd import synth
 
+import test_gpu_decode as GD
 import test_gpu_parity as G
 
 
@@ -18,8 +19,11 @@ def _variants_reached():
     layers = [synth.small_workload(h_q, h, d, w, k, n, h * Bh, dtype=dt) for h_q, h, d, w, k, n, Bh, dt in shapes]
     layers += [synth.small_workload(h_q, h, d, w, k, n, B, alpha=a, dtype=dt) for h_q, h, d, w, k, n, B, a, dt, _ in G._fuzz_shapes()]
     layers += [synth.workload(nm) for nm in ("tiny", "llama8b_32k", "llama8b_128k", "llama8b_ragged", "llama70b_128k")]
-    for wl in layers:
-        v = adakv.describe(adakv.Layer.from_workload(wl))
+    described = [adakv.describe(adakv.Layer.from_workload(wl)) for wl in layers]
+    for h_q, h, d, w, k, n, dt, _ in G.POOL_FIRST_CASES:
+        wl = synth.small_workload(h_q, h, d, w, k, n, [h * (w + 1)] * len(n), dtype=dt)
+        described.append(adakv.describe(adakv.Layer.from_workload(wl, flags=adakv.binding.ADAKV_FLAG_POOL_THEN_MEAN)))
+    for v in described:
         if v["score"] == "mfma":
             seen.add((v["dtype"], int(v["d"]), int(v["mb"]), int(v["rs"]), int(v["kg"]), int(v["chunk"])))
             seen.add(("lse", v["lse"], int(v["d"])))
@@ -39,7 +43,10 @@ def test_gpu_shapes_reach_every_scoring_variant(lib):
         want.add((dt, d, 2, 8, 1, 1024) if d == 128 else (dt, d, 4, 4, 1, 1024))
     for d in (64, 128):
         want |= {("lse", "fused", d), ("lse", "kernel", d), ("pool", "fused", d), ("pool", "kernel", d)}
-    want |= {("fma", "fp32", 64), ("fma", "fp32", 128)}
+    for dt, d in itertools.product(("bf16", "fp16", "fp32"), (64, 128)):
+        want.add(("fma", dt, d))
+        if (dt, d) != ("fp32", 128):            # the other order is the same kernel per type and d;
+            want.add(("fma-pool-first", dt, d)) # fp32 d = 128 is reached by the plain order only
     missing = sorted(map(str, want - seen))
     assert not missing, "no GPU parity shape reaches: " + ", ".join(missing)
 
@@ -59,3 +66,13 @@ def test_describe_follows_flags_and_rejects_what_score_rejects(lib):
         assert e.status == -1
     else:
         raise AssertionError("an even pool kernel must be rejected")
+
+
+def test_gpu_shapes_reach_every_decode_variant():
+    """decode_attn_kernel<T, D, G> and decode_combine_kernel<D, G> are instantiated per element
+    type, head dimension and group size; supported: three types, d 64 / 128, g 1 / 2 / 4 / 8."""
+    shapes = list(GD.DECODE_SHAPES) + [s for s, _, _ in GD.decode_sweep_shapes()] + list(GD.DECODE_VARIANT_SHAPES)
+    seen = {(dt, d, h_q // h) for h_q, h, d, _, _, _, dt, _ in shapes}
+    want = set(itertools.product((torch.bfloat16, torch.float16, torch.float32), (64, 128), (1, 2, 4, 8)))
+    missing = sorted(map(str, want - seen))
+    assert not missing, "no GPU decode shape reaches: " + ", ".join(missing)
