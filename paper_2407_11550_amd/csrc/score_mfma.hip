@@ -127,6 +127,9 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // once per workgroup, addressed as a wave-uniform 64-bit base (scalar registers) plus a
   // 32-bit per-lane offset.  The loads of iterations it+1 .. it+DEPTH are in flight while
   // iteration it is computed (DEPTH register sets, two LDS buffers, one barrier per iteration).
+#ifndef ADAKV_FUSED_TILE
+#define ADAKV_FUSED_TILE 1
+#endif
   // register sets = iterations of loads in flight (a third set fits the statistics sweep's
   // registers and was measured: no faster)
   constexpr int DEPTH = 2;
@@ -353,6 +356,68 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
       if (half == 0) sh_part[rs][tile * TILE + l32] = sum;   // key k0 + tile*TILE + l32
     }
   };
+  // The common case of the loop below in one piece: the matrix instructions of the current tile
+  // with the vector arithmetic of the previous (full) tile dealt out between them, a share in
+  // front of every MFMA (the first share covers the wait for the tile's LDS operands), and a scheduling fence after every share so that the order survives: an MFMA
+  // runs for tens of cycles in the matrix core while the wavefront goes on issuing vector
+  // instructions, but only if vector instructions follow it in program order.
+  auto fused_tile = [&](const bf16x8 (&kf)[KS], floatx16 (&accn)[MB], floatx16 (&acc)[MB], int tile) {
+    constexpr int SLOTS = MB * KS;               // matrix instructions per tile
+    constexpr int VALS = MB * 16;                // products of the previous tile per lane
+    floatx16 a[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) a[mb] = floatx16{0};
+    if (PASS == 1) {
+      // slots 0 .. MB-1 find the row blocks' tile maxima, the others share the exponentials
+      constexpr int ESLOTS = SLOTS - MB;
+      float ref[MB], nmx[MB], sum[MB];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const int slot = s * MB + mb;
+          if (slot < MB) {
+            float tm = acc[slot][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[slot][r]);
+            nmx[slot] = fmaxf(rm[slot], tm * c_log2);
+            ref[slot] = (nmx[slot] == -INFINITY) ? 0.0f : nmx[slot];
+            sum[slot] = 0.0f;
+          } else {
+            const int e = slot - MB;
+#pragma unroll
+            for (int v = e * VALS / ESLOTS; v < (e + 1) * VALS / ESLOTS; ++v)
+              sum[v / 16] += fast_exp2(fmaf(acc[v / 16][v % 16], c_log2, -ref[v / 16]));
+          }
+          a[mb] = mfma16<F16>(kf[s], qf[mb][s], a[mb]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        rl[mb] = rl[mb] * fast_exp2(rm[mb] - ref[mb]) + sum[mb];
+        rm[mb] = nmx[mb];
+      }
+    } else {
+      float sum = 0.0f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const int slot = s * MB + mb;
+#pragma unroll
+          for (int v = slot * VALS / SLOTS; v < (slot + 1) * VALS / SLOTS; ++v)
+            sum += fast_exp2(fmaf(acc[v / 16][v % 16], c_log2, -l2[v / 16][v % 16]));
+          a[mb] = mfma16<F16>(qf[mb][s], kf[s], a[mb]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      sum += __shfl_xor(sum, 32);
+      if (half == 0) sh_part[rs][tile * TILE + l32] = sum;   // key k0 + tile*TILE + l32
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) accn[mb] = a[mb];
+  };
   auto is_full = [&](int tile) { return k0 + tile * TILE + TILE <= n; };
 
   floatx16 accp[MB];                                   // products of the tile before the current one
@@ -373,8 +438,12 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     if (have && prev_tile >= 0 && is_full(prev_tile)) {
       // the common case, straight-line: products of this tile, arithmetic of the previous one
       floatx16 accn[MB];
-      mma(kf, accn);
-      epilogue(std::false_type{}, accp, prev_tile);
+      if (ADAKV_FUSED_TILE) {
+        fused_tile(kf, accn, accp, prev_tile);
+      } else {
+        mma(kf, accn);
+        epilogue(std::false_type{}, accp, prev_tile);
+      }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) accp[mb] = accn[mb];
       prev_tile = tile;
