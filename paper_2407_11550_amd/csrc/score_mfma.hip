@@ -131,7 +131,8 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
 #define ADAKV_FUSED_TILE 1
 #endif
   // register sets = iterations of loads in flight (a third set fits the statistics sweep's
-  // registers and was measured: no faster)
+  // registers and was measured: no faster; nor are four or six sets on the 512-row shape,
+  // where a set is a single word per thread)
   constexpr int DEPTH = 2;
   constexpr int TW = TILE * ROW16;                     // 16-byte words per tile
   constexpr int LDPT = KG * TW / NT;                   // loads per thread per iteration
