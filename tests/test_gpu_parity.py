@@ -287,6 +287,20 @@ def test_full_size_layer(name, alpha):
     _say(f"  budgets min {bud.min()} max {bud.max()}")
 
 
+def test_very_long_sequence_folds_the_partial_statistics_in_several_rounds():
+    """600 000 prefix tokens with 4 window rows per head: 293 chunks of statistics per head, more
+    than one round (256) of the fused combination in the weights sweep, and 147 emit blocks per
+    head.  Whole output compared."""
+    _say("very long sequence")
+    wl = synth.small_workload(2, 2, 128, 4, 7, 600_000, 2 * (4 + 9000), seed=91)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer, out = _run(wl, q, K, V)
+    v = adakv.describe(layer)
+    assert v["lse"] == "fused" and v["chunk"] == "2048"
+    _say("  gpu done, oracle running")
+    _check_all(wl, q, K, V, out)
+
+
 def test_full_size_ragged_batch_one_layer():
     # batch 8, prefix lengths drawn from [4096, 65536], budgets 5 % of n per head, packed layout:
     # one of the 32 layers of the ragged workload, every sequence compared in full
