@@ -130,9 +130,14 @@ def test_decode_attn_empty_segment_and_custom_scale():
     assert not out[0, 4:].any() and torch.isneginf(lse[0, 4:]).all()
 
 
-def test_cache_build_is_the_gather_with_head_room_bit_exact():
-    _say("cache_build")
-    wl = synth.small_workload(8, 2, 128, 8, 7, [700, 300], [2 * 90, 2 * 40], seed=9)
+ROW_WIDTHS = [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float16, 64), (torch.float32, 64), (torch.float32, 128)]
+ROW_IDS = ["bf16_d128", "bf16_d64", "fp16_d64", "fp32_d64", "fp32_d128"]     # rows of 256, 128, 128, 256, 512 bytes
+
+
+@pytest.mark.parametrize("dt,d", ROW_WIDTHS, ids=ROW_IDS)
+def test_cache_build_is_the_gather_with_head_room_bit_exact(dt, d):
+    _say(f"cache_build {dt} d {d}")
+    wl = synth.small_workload(8, 2, d, 8, 7, [700, 300], [2 * 90, 2 * 40], dtype=dt, seed=9)
     q, K, V = synth.generate(wl, device=DEV)
     layer = adakv.Layer.from_workload(wl)
     res = adakv.compress(layer, q, K, V)
@@ -154,9 +159,10 @@ def test_cache_build_is_the_gather_with_head_room_bit_exact():
     assert (gK[~used] == -7.0).all() and (gV[~used] == -9.0).all()          # nothing else was written
 
 
-def test_append_then_attend_matches_oracle_step_by_step_and_reports_overflow():
-    _say("append + decode chain")
-    wl = synth.small_workload(8, 2, 128, 8, 7, [700, 300], [2 * 90, 2 * 40], seed=13)
+@pytest.mark.parametrize("dt,d", ROW_WIDTHS, ids=ROW_IDS)
+def test_append_then_attend_matches_oracle_step_by_step_and_reports_overflow(dt, d):
+    _say(f"append + decode chain {dt} d {d}")
+    wl = synth.small_workload(8, 2, d, 8, 7, [700, 300], [2 * 90, 2 * 40], dtype=dt, seed=13)
     q, K, V = synth.generate(wl, device=DEV)
     layer = adakv.Layer.from_workload(wl)
     res = adakv.compress(layer, q, K, V)
