@@ -199,6 +199,10 @@ def main():
                          "decode attention over the compressed cache")
     ap.add_argument("--budget-frac", type=float, default=None,
                     help="decode path: keep this fraction of every prefix instead of the workload's budget")
+    ap.add_argument("--pyramid", type=float, default=None, metavar="RATIO",
+                    help="compress path: treat the --sets input sets as consecutive layers and give them the "
+                         "pyramidal variant's budgets (adakv_pyramid_budgets, first layer RATIO times the last, "
+                         "mean = the workload's budget); not the headline configuration")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device-to-device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -222,6 +226,17 @@ def main():
     layer = adakv.Layer.from_workload(wl)
     sets = [synth.generate(wl, layer=i, device=dev) for i in range(args.sets)]
     lses = [synth.prefill_row_lse(wl, q, K) if args.row_lse else None for q, K, _ in sets]
+    # one layer description per input set: all alike, or the pyramidal variant's budgets per layer
+    layers = [layer] * args.sets
+    if args.pyramid is not None:
+        wh = wl.w * wl.h_kv
+        per_seq = [adakv.pyramid_budgets(args.sets, Bb - wh, args.pyramid) for Bb in wl.B]
+        layers = []
+        for l in range(args.sets):
+            wll = synth.workload(args.workload, alpha=args.alpha)
+            wll.B = [min(per_seq[b][l], wl.h_kv * wl.n[b]) + wh for b in range(wl.batch)]
+            layers.append(adakv.Layer.from_workload(wll))
+        layer = max(layers, key=lambda L: L.num_rows_out)          # sizes the output buffers
     def make_bufs():
         return (torch.empty(adakv.workspace_bytes(layer), dtype=torch.uint8, device=dev),
                 dict(scores=torch.empty(layer.num_scores, dtype=torch.float32, device=dev),
@@ -242,8 +257,8 @@ def main():
     def step(i):
         q, K, V = sets[i % len(sets)]
         lane_ws, lane_bufs = lanes[i % len(lanes)]
-        return adakv.compress(layer, q, K, V, row_lse=lses[i % len(sets)], ws=lane_ws, bufs=lane_bufs,
-                              stream=streams[i % len(streams)])
+        return adakv.compress(layers[i % len(sets)], q, K, V, row_lse=lses[i % len(sets)], ws=lane_ws,
+                              bufs=lane_bufs, stream=streams[i % len(streams)])
 
     for i in range(args.warmup):
         step(i)
@@ -261,7 +276,7 @@ def main():
     trace_steps = min(args.steps, 50)
     per_kernel, order = traced_pass(adakv, torch, step, trace_steps, kernels_per_step=16)
     kernels = {k: float(np.mean(v)) for k, v in per_kernel.items()}
-    kept = layer.num_rows_out
+    kept = int(np.mean([L.num_rows_out for L in layers]))
     alg = algorithmic_bytes(wl, kept)
     dominant = max(kernels, key=kernels.get)
     # bytes one launch of the dominant kernel has to move: a scoring sweep reads K once
@@ -353,6 +368,8 @@ def main():
                    "w": wl.w, "pool_k": wl.pool_k, "B": wl.B, "alpha": wl.alpha, "batch": wl.batch,
                    "input_sets_rotated": len(sets),
                    "row_lse": "supplied by the caller (single sweep)" if args.row_lse else "computed (two sweeps)",
+                   "layer_budgets": "equal" if args.pyramid is None else
+                   f"pyramid over {args.sets} layers, ratio {args.pyramid}: " + str([L.num_rows_out for L in layers]),
                    "layers_in_flight": max(1, args.streams)},
         "pipeline_hbm_frac": round(total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "pipeline_algorithmic_bytes": total_alg,

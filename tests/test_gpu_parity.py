@@ -287,6 +287,27 @@ def test_full_size_layer(name, alpha):
     _say(f"  budgets min {bud.min()} max {bud.max()}")
 
 
+def test_pyramid_schedule_feeds_the_layer_budgets():
+    """The pyramidal variant (Section 3.4) only changes the budget each layer gets: six layers of
+    one shape, budgets from adakv_pyramid_budgets (largest first, mean = the average budget),
+    every layer compressed with its own B and compared with the oracle."""
+    _say("pyramid schedule")
+    h, w, n, layers, per_head = 4, 8, 2600, 6, 150
+    prefix = adakv.pyramid_budgets(layers, h * per_head, 3.0)       # B' of each layer
+    assert prefix == O.pyramid_budgets(layers, h * per_head, 3.0)
+    assert sum(prefix) == layers * h * per_head and all(a >= b for a, b in zip(prefix, prefix[1:]))
+    assert prefix[0] > 2 * prefix[-1]
+    kept = []
+    for l, bp in enumerate(prefix):
+        wl = synth.small_workload(8, h, 128, w, 7, n, h * w + bp, seed=70)
+        q, K, V = synth.generate(wl, layer=l, device=DEV)
+        _, out = _run(wl, q, K, V)
+        _check_all(wl, q, K, V, out)
+        assert int(out["budgets"].sum()) == bp
+        kept.append(int(out["cu_seqlens"][-1]))
+    assert kept == [bp + h * w for bp in prefix]
+
+
 def test_very_long_sequence_folds_the_partial_statistics_in_several_rounds():
     """600 000 prefix tokens with 4 window rows per head: 293 chunks of statistics per head, more
     than one round (256) of the fused combination in the weights sweep, and 147 emit blocks per
