@@ -73,3 +73,39 @@ def test_fused_pool_reads_stay_inside_the_chunk_array(chunk_len, nt):
         for pool_r in [0, 1, 3, 16, 32]:
             for halo in (0, 1):
                 assert pool_violations(n, chunk_len, nt, pool_r, halo) == 0, (n, pool_r, halo)
+
+
+def interleaved_violations(n, chunk_len, kg):
+    """Sweep 1: workgroup `chunk` of the nch = ceil(n / chunk_len) of a head takes the tile sets
+    chunk, chunk + nch, ... of the whole sequence (a set = kg tiles of 32 keys).  Every set must be
+    taken exactly once, every workgroup must have at least one, no set may start past the last
+    key, and the row clamp (0 .. n-1-key0) must keep every lane inside the sequence."""
+    bad = 0
+    nch = (n + chunk_len - 1) // chunk_len
+    ntiles = (n + TILE - 1) // TILE
+    sets_all = (ntiles + kg - 1) // kg
+    taken = [0] * sets_all
+    for chunk in range(nch):
+        iters = (sets_all - chunk + nch - 1) // nch
+        bad += iters < 1
+        for it in range(iters):
+            s = chunk + it * nch
+            bad += not (0 <= s < sets_all)
+            if 0 <= s < sets_all:
+                taken[s] += 1
+            key0 = s * kg * TILE
+            bad += key0 > n - 1
+            lim = max(n - 1 - key0, 0)
+            for rel in range(kg * TILE):
+                row = max(min(rel, lim), 0)
+                bad += not (0 <= key0 + row < n)
+                bad += key0 + rel < n and row != rel
+    bad += any(t != 1 for t in taken)
+    return bad
+
+
+@pytest.mark.parametrize("chunk_len", [512, 1024, 2048])
+@pytest.mark.parametrize("kg", [1, 2, 4])
+def test_interleaved_sets_of_sweep_one_cover_every_key_once(chunk_len, kg):
+    for n in [1, 5, 31, 32, 33, 63, 64, 65, 300, 511, 512, 513, 2047, 2048, 2049, 2080, 4096, 4099, 6000, 6145, 20001]:
+        assert interleaved_violations(n, chunk_len, kg) == 0, n
