@@ -207,13 +207,16 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
   __shared__ int sh_sure;
   const int tid = threadIdx.x;
   const int b = find_seq(ct, st.batch, blockIdx.x);
-  const int chunk = blockIdx.x - ct.off[b];
+  // the first sequence's facts sit at fixed places of the kernel arguments and arrive with the
+  // first scalar fetch; only later sequences of a batch cost a dependent one
+  int n = st.n[0], cfirst = ct.off[0], soff = st.score_off[0];
+  if (b != 0) { n = st.n[b]; cfirst = ct.off[b]; soff = st.score_off[b]; }
+  const int chunk = blockIdx.x - cfirst;
   const int c = blockIdx.y;
-  const int n = st.n[b];
   const int nsegs = st.batch * h;
   // the block's scores are requested first, so they arrive while the prologue below waits for
   // the previous pass's histogram (indices past the end are clamped, the values ignored)
-  const float *row = scores + st.score_off[b] + (size_t)c * n;
+  const float *row = scores + soff + (size_t)c * n;
   const int j0 = chunk * SEL_CHUNK;
   const int j1 = min(n, j0 + SEL_CHUNK);
   constexpr int EPB = SEL_CHUNK / 256;
@@ -411,12 +414,13 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
   __shared__ int sh_base[2];
   const int tid = threadIdx.x;
   const int b = find_seq(ct, st.batch, blockIdx.x);
-  const int chunk = blockIdx.x - ct.off[b];
+  int n = st.n[0], cfirst = ct.off[0], soff = st.score_off[0];   // as in the histogram kernel
+  if (b != 0) { n = st.n[b]; cfirst = ct.off[b]; soff = st.score_off[b]; }
+  const int chunk = blockIdx.x - cfirst;
   const int c = blockIdx.y;
-  const int n = st.n[b];
   const int seg = b * h + c;
   const int out0 = cu[seg];
-  const float *row = scores + st.score_off[b] + (size_t)c * n;
+  const float *row = scores + soff + (size_t)c * n;
 
   // this thread's 16 consecutive positions (loads issued before the scans below)
   const int j0 = chunk * SEL_CHUNK + tid * EPT;
@@ -430,12 +434,12 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
   // do not depend on the threshold, so they are issued in front of its scan, 32 chunks at a time.
   constexpr int CB = 32;   // 32 chunks = 131072 positions of a head in one round trip
   int pg = 0, pe = 0;
-  for (int k = tid; k < chunk; k += 256) pg += chunk_sure[(size_t)(ct.off[b] + k) * h + c];
+  for (int k = tid; k < chunk; k += 256) pg += chunk_sure[(size_t)(cfirst + k) * h + c];
   uint2 first[CB];
 #pragma unroll
   for (int u = 0; u < CB; ++u) {
     const int k = min(u, max(chunk - 1, 0));
-    first[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(ct.off[b] + k) * h + c) * 1024 + tid * 4);
+    first[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(cfirst + k) * h + c) * 1024 + tid * 4);
   }
   if (tid < 2) sh_base[tid] = 0;
   const Rank r = head_threshold(st, h, b, c, hist, state, sh);
@@ -462,7 +466,7 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
 #pragma unroll
       for (int u = 0; u < CB; ++u) {
         const int k = min(k0c + u, chunk - 1);
-        more[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(ct.off[b] + k) * h + c) * 1024 + tid * 4);
+        more[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(cfirst + k) * h + c) * 1024 + tid * 4);
       }
 #pragma unroll
       for (int u = 0; u < CB; ++u)
