@@ -32,7 +32,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # (workload, kernel) -> fetched + written bytes per launch, see profiles/llama8b_128k_hbm_traffic.md
 # and profiles/decode_llama8b_ragged_hbm_traffic.md
 MEASURED_TRAFFIC_BYTES = {
-    ("llama8b_128k", "score_stats_mfma"): int((256.41 + 0.90) * 2 ** 20),
+    ("llama8b_128k", "score_stats_mfma"): int((256.39 + 0.90) * 2 ** 20),
     ("llama8b_128k", "score_weights_mfma"): int((257.04 + 4.10) * 2 ** 20),
     ("llama8b_ragged/decode", "decode_attn"): int((44.86 + 1.03) * 2 ** 20),
 }
