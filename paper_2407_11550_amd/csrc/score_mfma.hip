@@ -1,16 +1,18 @@
-// Observation-window scoring (Alg. 2 lines 1-5, group mean of Section 3.5) for bf16 inputs on
-// the gfx950 matrix cores: logits = Q_win K^T as v_mfma_f32_32x32x16_bf16 tiles with fp32
+// Observation-window scoring (Alg. 2 lines 1-5, group mean of Section 3.5) for bf16 and fp16
+// inputs on the gfx950 matrix cores: logits = Q_win K^T as v_mfma_f32_32x32x16 tiles with fp32
 // accumulation, softmax and reductions in fp32 on the vector ALUs.
 //
 // The softmax of Alg. 2 l.3 needs every window row's denominator before the rows of a head can
 // be added up, so K is swept twice:
 //   sweep 1 (PASS 1)  per-row (max, sum of exp) over the keys        -> partial statistics
 //   sweep 2 (PASS 2)  exp(logit - lse) summed over the g*w rows      -> pre-pool scores
-// Sweep 2 walks every chunk backwards from the point where sweep 1 started (and ended) it, so it
-// begins with what sweep 1 left in the memory-side cache.  A caller-supplied row_lse skips sweep 1.
+// A caller-supplied row_lse skips sweep 1.
 //
-// Work split.  A workgroup owns CHUNK consecutive keys of one KV head; all g query heads of the
-// group share every K tile.  A wavefront keeps at most 64 window rows of Q in registers as MFMA
+// Work split.  In sweep 2 a workgroup owns CHUNK consecutive keys of one KV head (the fused
+// max-pool wants neighbours); in sweep 1 the workgroups of a head take the head's tile sets in
+// turn (set c, c + nch, ...), because a (max, sum) pair does not care which keys it saw and the
+// chip then streams one dense region of K at a time.  All g query heads of the group share
+// every K tile.  A wavefront keeps at most 64 window rows of Q in registers as MFMA
 // operands for the whole chunk (MB blocks of 32 rows), which leaves room for two wavefronts per
 // SIMD, so one wavefront's exponentials overlap the other's matrix work.  RS wavefronts split
 // the rows of a head, and the KG = NW/RS groups of wavefronts take the 32-key tiles of the
