@@ -233,6 +233,36 @@ def test_select_long_heads_take_the_chunk_parallel_emit():
         assert np.array_equal(idx, O.select(s, rb, w))
 
 
+@pytest.mark.parametrize("dt,d,layout", [(torch.bfloat16, 128, "fused_kv"), (torch.float16, 64, "padded_head"),
+                                          (torch.float32, 64, "fused_kv"), (torch.bfloat16, 128, "padded_head")])
+def test_whole_step_on_strided_k_and_v(dt, d, layout):
+    """K and V as views into larger tensors: K and V of a token side by side in one row
+    ([token][2][head][d], token stride 2*h*d), or a head dimension padded to d + 16 elements.  The
+    whole step must give what it gives on contiguous copies of the same values."""
+    _say(f"strided K/V {dt} {d} {layout}")
+    h_q, h, w, n = 8, 2, 16, [2300, 700]
+    wl = synth.small_workload(h_q, h, d, w, 7, n, [h * (w + 150), h * (w + 60)], dtype=dt, seed=44)
+    q, K, V = synth.generate(wl, device=DEV)
+    rows = K.shape[0]
+    if layout == "fused_kv":
+        both = torch.empty((rows, 2, h, d), dtype=dt, device=DEV)
+        both[:, 0], both[:, 1] = K, V
+        Ks, Vs = both[:, 0], both[:, 1]
+        strides = dict(k_strides=(2 * h * d, d), v_strides=(2 * h * d, d))
+    else:
+        Kp = torch.full((rows, h, d + 16), 3.0, dtype=dt, device=DEV)
+        Vp = torch.full((rows, h, d + 16), -3.0, dtype=dt, device=DEV)
+        Kp[:, :, :d], Vp[:, :, :d] = K, V
+        Ks, Vs = Kp[:, :, :d], Vp[:, :, :d]
+        strides = dict(k_strides=(h * (d + 16), d + 16), v_strides=(h * (d + 16), d + 16))
+    plain = adakv.compress(adakv.Layer.from_workload(wl), q, K, V)
+    out = adakv.compress(adakv.Layer.from_workload(wl, **strides), q, Ks, Vs)
+    torch.cuda.synchronize()
+    for key in plain:
+        assert torch.equal(plain[key], out[key]), key
+    _check_all(wl, q, K, V, out)
+
+
 # ------------------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("dt,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)])
 def test_compact_bit_exact_with_strides_and_canaries(dt, d):
