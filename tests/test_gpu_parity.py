@@ -263,6 +263,45 @@ def test_whole_step_on_strided_k_and_v(dt, d, layout):
     _check_all(wl, q, K, V, out)
 
 
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float32], ids=["bf16", "fp32"])
+def test_loose_packing_and_a_caller_scale(dt):
+    """Sequences need not be packed tightly (tok_off may leave rows between them, here 37 and 5 rows
+    of NaN that must never be read) and the logit scale may be the caller's (Section 3.1's footnote
+    only says that 1/sqrt(d) is left out of the formulas)."""
+    _say(f"loose packing, scale {dt}")
+    h_q, h, d, w = 8, 2, 128 if dt == torch.bfloat16 else 64, 8
+    n, B = [1900, 640, 33], [h * (w + 120), h * (w + 50), h * (w + 9)]
+    wl = synth.small_workload(h_q, h, d, w, 5, n, B, dtype=dt, seed=61)
+    q, K, V = synth.generate(wl, device=DEV)
+    gaps = [37, 5, 0]
+    off = [0]
+    for nb, gp in zip(n, gaps):
+        off.append(off[-1] + nb + w + gp)
+    Kl = torch.full((off[-1], h, d), float("nan"), dtype=dt, device=DEV)
+    Vl = torch.full((off[-1], h, d), float("nan"), dtype=dt, device=DEV)
+    for b in range(len(n)):
+        rows = n[b] + w
+        Kl[off[b]:off[b] + rows] = K[wl.tok_off[b]:wl.tok_off[b] + rows]
+        Vl[off[b]:off[b] + rows] = V[wl.tok_off[b]:wl.tok_off[b] + rows]
+    scale = 0.11
+    layer = adakv.Layer.from_workload(wl, scale=scale)
+    layer_loose = adakv.Layer(dt, h_q, h, d, w, 5, wl.alpha, n, B, tok_off=off, scale=scale)
+    tight = adakv.compress(layer, q, K, V)
+    loose = adakv.compress(layer_loose, q, Kl, Vl)
+    torch.cuda.synchronize()
+    for key in tight:
+        assert torch.equal(tight[key], loose[key]), key
+    assert torch.isfinite(loose["scores"]).all() and torch.isfinite(loose["K_out"].float()).all()
+    soff = 0
+    for b in range(len(n)):
+        ref = oracle_layer(wl, q, K, V, b, scale=scale)
+        ns = h * n[b]
+        assert_scores_close(tight["scores"][soff:soff + ns].cpu().numpy(), ref["scores"], f"scaled seq {b}")
+        soff += ns
+    other = adakv.score(adakv.Layer.from_workload(wl), q, K)
+    assert not torch.equal(other, tight["scores"])                # the scale is really applied
+
+
 # ------------------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("dt,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)])
 def test_compact_bit_exact_with_strides_and_canaries(dt, d):
