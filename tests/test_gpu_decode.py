@@ -373,3 +373,26 @@ DECODE_VARIANT_SHAPES = [
 def test_every_decode_variant_matches_oracle(shape):
     _say(f"decode variant {shape}")
     _two_fused_steps(shape, seed=55, skew=1.5)
+
+
+def test_decode_attn_clamps_corrupt_segment_lengths():
+    """A length below zero counts as empty, a length beyond the segment's capacity as full: the
+    kernel never reads outside the segment (the cache is followed by NaN rows that must not show)."""
+    _say("decode_attn with corrupt lengths")
+    hr = 3
+    wl, layer, Kc, Vc, cu, seg_len = _decode_case(8, 2, 128, 4, [400, 90], 60, torch.bfloat16, hr, seed=6)
+    rows = Kc.shape[0]
+    Kbig = torch.full((rows + 64, wl.d), float("nan"), dtype=Kc.dtype, device=DEV)
+    Vbig = torch.full_like(Kbig, float("nan"))
+    Kbig[:rows], Vbig[:rows] = Kc, Vc
+    bad = seg_len.clone()
+    bad[0], bad[1], bad[3] = -7, 10 ** 6, 2 ** 31 - 1
+    q, _, _ = synth.decode_inputs(wl, 1, seed=6, device=DEV)
+    out, lse = adakv.decode_attn(layer, q[0], cu, hr, Kbig[:rows], Vbig[:rows], bad, want_lse=True)
+    torch.cuda.synchronize()
+    cuh = cu.cpu().numpy()
+    cap = (cuh[1:] - cuh[:-1]) + hr
+    lens = np.clip(bad.cpu().numpy().astype(np.int64), 0, cap)
+    ref_out, ref_lse = D.decode_attention(to_f64(q[0]), to_f64(Kc), to_f64(Vc), cuh, hr, lens, wl.g)
+    assert torch.isfinite(out).all()
+    _assert_decode_close(out, lse, ref_out, ref_lse, float(Vc.float().abs().max()) + 1.0, "corrupt lengths")

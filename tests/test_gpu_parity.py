@@ -649,3 +649,50 @@ def test_streaming_read_probe_reads_every_word_once(nbytes):
     assert np.array_equal(got, want)
     with pytest.raises(adakv.AdaKVError):
         adakv.probe_read(torch.zeros(6, dtype=torch.int32, device=DEV), sink)      # 24 bytes
+
+
+# ------------------------------------------------------------------ out-of-contract data
+def test_compact_clamps_indices_that_leave_the_sequence():
+    """A corrupt index must not take the gather outside the sequence's own rows: it is clamped to
+    [0, n + w - 1] (the rows around K and V hold NaN and must not show up in the outputs)."""
+    _say("compact with corrupt indices")
+    h, n, w, d = 2, 300, 4, 128
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    pad = 50
+    Kbig = torch.full((pad + n + w + pad, h, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    Vbig = torch.full_like(Kbig, float("nan"))
+    Kbig[pad:pad + n + w] = torch.randn((n + w, h, d), generator=g, device=DEV).to(torch.bfloat16)
+    Vbig[pad:pad + n + w] = torch.randn((n + w, h, d), generator=g, device=DEV).to(torch.bfloat16)
+    K, V = Kbig[pad:pad + n + w], Vbig[pad:pad + n + w]
+    budgets = np.array([6, 3], np.int32)
+    cu = np.concatenate([[0], np.cumsum(budgets + w)]).astype(np.int32)
+    idx = np.array([0, -5, 10 ** 9, n + w + 100, 17, -(2 ** 31), n, n + 1, n + 2, n + 3,
+                    5, 2 ** 31 - 1, -1, n, n + 1, n + 2, n + 3], np.int32)
+    assert len(idx) == cu[-1]
+    layer = adakv.Layer(torch.bfloat16, h, h, d, w, 7, 0.2, [n], [int(cu[-1])])
+    Ko, Vo = adakv.compact(layer, K, V, torch.tensor(idx, device=DEV), torch.tensor(cu, device=DEV))
+    torch.cuda.synchronize()
+    clamped = np.clip(idx.astype(np.int64), 0, n + w - 1)
+    Kr, Vr = O.compact(K.float().cpu().numpy(), V.float().cpu().numpy(), clamped, cu)
+    assert np.array_equal(Ko.float().cpu().numpy(), Kr) and np.array_equal(Vo.float().cpu().numpy(), Vr)
+
+
+def test_select_with_inconsistent_budgets_stays_inside_its_output():
+    """Budgets that ask for more than a head holds, or for less than nothing, and offsets that do
+    not match them: the result is unspecified, but nothing outside indices[0 .. sum B) is written."""
+    _say("select with corrupt budgets")
+    rng = np.random.default_rng(12)
+    h, n, w = 3, 6000, 4
+    s = rng.random((h, n)).astype(np.float32)
+    good = np.array([40, 50, 60], np.int32)
+    cu = np.concatenate([[0], np.cumsum(good + w)]).astype(np.int32)
+    rows = int(cu[-1])
+    layer = adakv.Layer(torch.bfloat16, h, h, 128, w, 7, 0.2, [n], [rows])
+    for budgets, offsets in (([n + 500, -3, 50], cu), ([40, 50, 60], [0, 10 ** 6, -7, 5]), ([2 ** 30, 2 ** 30, 2 ** 30], cu)):
+        big = torch.full((rows + 16,), -77, dtype=torch.int32, device=DEV)
+        adakv.select(layer, torch.tensor(s, device=DEV).reshape(-1), torch.tensor(budgets, dtype=torch.int32, device=DEV),
+                     torch.tensor(np.asarray(offsets, np.int32), device=DEV), indices=big[8:8 + rows])
+        torch.cuda.synchronize()
+        assert (big[:8] == -77).all() and (big[8 + rows:] == -77).all(), budgets
+        inside = big[8:8 + rows]
+        assert ((inside == -77) | ((inside >= 0) & (inside < n + w))).all(), budgets
