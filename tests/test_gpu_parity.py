@@ -391,12 +391,13 @@ def test_very_long_sequence_folds_the_partial_statistics_in_several_rounds():
     _check_all(wl, q, K, V, out)
 
 
-def test_full_size_ragged_batch_one_layer():
+@pytest.mark.parametrize("layer_no", [3, 17, 31])
+def test_full_size_ragged_batch_one_layer(layer_no):
     # batch 8, prefix lengths drawn from [4096, 65536], budgets 5 % of n per head, packed layout:
-    # one of the 32 layers of the ragged workload, every sequence compared in full
-    _say("full size ragged batch")
+    # three of the 32 layers of the ragged workload, every sequence compared in full
+    _say(f"full size ragged batch, layer {layer_no}")
     wl = synth.workload("llama8b_ragged")
-    q, K, V = synth.generate(wl, layer=3, device=DEV)
+    q, K, V = synth.generate(wl, layer=layer_no, device=DEV)
     _, out = _run(wl, q, K, V)
     _say(f"  gpu done, n = {wl.n}")
     _check_all(wl, q, K, V, out)
