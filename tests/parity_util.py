@@ -19,6 +19,22 @@ def oracle_layer(wl, q, K, V, b=0, **kw):
                             wl.pool_k, wl.B[b], wl.alpha, **kw)
 
 
+def oracle_batch(wl, q, K, V, **kw):
+    """The oracle on the whole packed batch (O.compress_batch), plus, per sequence, the same
+    outputs cut back out with offsets made relative to the sequence."""
+    ref = O.compress_batch(to_f64(q), to_f64(K), V.float().cpu().numpy(), wl.n, wl.B, wl.tok_off[:-1],
+                           wl.w, wl.pool_k, wl.alpha, **kw)
+    h, per_seq, s0, row0 = wl.h_kv, [], 0, 0
+    for b in range(wl.batch):
+        per_seq.append(dict(scores=ref["scores"][s0:s0 + h * wl.n[b]].reshape(h, wl.n[b]),
+                            budgets=ref["budgets"][b * h:(b + 1) * h],
+                            cu_seqlens=ref["cu_seqlens"][b * h:(b + 1) * h + 1] - row0,
+                            indices=ref["indices"][row0:row0 + wl.B[b]]))
+        s0 += h * wl.n[b]
+        row0 += wl.B[b]
+    return ref, per_seq
+
+
 def assert_scores_close(gpu, ref, what=""):
     gpu = np.asarray(gpu, np.float64).reshape(-1)
     ref = np.asarray(ref, np.float64).reshape(-1)

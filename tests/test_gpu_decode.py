@@ -308,6 +308,66 @@ def test_eviction_loss_adaptive_against_uniform_allocation():
     assert sum(a < u for a, u in zip(losses[0.2], losses[1.0])) >= 5      # on most samples
 
 
+def test_eviction_loss_of_the_gpu_path_matches_the_oracle():
+    """Section 3.2 on the GPU path against the oracle: with one observation row, no pooling and
+    no GQA the scores are the attention weights A_i of the query over the n cache elements, the
+    selection is the decision I_i, and decode attention over the retained rows (the window row
+    left out of every segment by handing the kernel the budgets as segment lengths) is Eq. (5).
+    The oracle gets the same tensors and the GPU's decision and returns ||y - y_hat||_1 and
+    epsilon (Eqs. 4-6); the GPU's loss, formed from its own per-head attention outputs and a
+    random W^O on the host, must agree, its retained weight must be the oracle's
+    (2hC - epsilon) / 2C, and the loss must respect the bound (Theorem 3.1).
+    Tolerances: a GPU output element is within 5e-6 max|V| + 1e-4 |element| of the exact one
+    (this file's bar), both y and y_hat carry that, and the projection sums h*d of them with
+    weights |W^O|; the retained weight is a sum of scores, each within 2e-3 relative."""
+    h, d, n, dm = 8, 128, 3000, 32
+    rng = np.random.default_rng(5)
+    for seed, alpha in ((200, 0.0), (201, 0.2), (202, 1.0)):
+        _say(f"eviction loss against the oracle: seed {seed} alpha {alpha}")
+        wl = synth.small_workload(h, h, d, 1, 1, [n], [h * (1 + 90)], alpha=alpha, seed=seed,
+                                  temps=(0.5, 6.0), planted=(4, 200))
+        q, K, V = synth.generate(wl, device=DEV)
+        layer = adakv.Layer.from_workload(wl)
+        res = adakv.compress(layer, q, K, V)
+        Kc, Vc, _ = adakv.cache_build(layer, K, V, res["indices"], res["cu_seqlens"], 0)
+        qn = q[:, :, 0, :].contiguous()
+        out_c = adakv.decode_attn(layer, qn, res["cu_seqlens"], 0, Kc, Vc, res["budgets"].contiguous())
+        wl_full = synth.small_workload(h, h, d, 1, 1, [n], [h * (1 + n)], alpha=alpha, seed=seed,
+                                       temps=(0.5, 6.0), planted=(4, 200))
+        lf = adakv.Layer.from_workload(wl_full)
+        rf = adakv.compress(lf, q, K, V)
+        Kf, Vf, _ = adakv.cache_build(lf, K, V, rf["indices"], rf["cu_seqlens"], 0)
+        out_f = adakv.decode_attn(lf, qn, rf["cu_seqlens"], 0, Kf, Vf, rf["budgets"].contiguous())
+        torch.cuda.synchronize()
+        assert int(rf["budgets"].min()) == n                       # the full cache really holds every row
+        # the decision, from the GPU's indices (prefix positions only)
+        keep = np.zeros((h, n), bool)
+        idx, cu, bud = res["indices"].cpu().numpy(), res["cu_seqlens"].cpu().numpy(), res["budgets"].cpu().numpy()
+        for c in range(h):
+            keep[c, idx[cu[c]:cu[c] + bud[c]]] = True
+        assert keep.sum() == bud.sum() == wl.B[0] - h
+        WO = rng.standard_normal((h, d, dm))
+        Kd, Vd = to_f64(K[:n]), to_f64(V[:n])
+        scale = 1.0 / np.sqrt(d)                                   # the oracle's Section 3.1 form has no scale: fold it into q
+        loss_o, eps_o = O.eviction_loss_and_bound(to_f64(qn[0]) * scale, Kd, Vd, WO, keep)
+        y_g = sum(to_f64(out_f[0, c]) @ WO[c] for c in range(h))
+        yh_g = sum(to_f64(out_c[0, c]) @ WO[c] for c in range(h))
+        loss_g = float(np.abs(y_g - yh_g).sum())
+        vmax = float(np.abs(Vd).max())
+        wabs = np.abs(WO).sum(axis=2)                                # [h, d]: weight of an output element in the L1 norm
+        tol = float(((2 * OUT_ATOL_PER_VMAX * vmax + OUT_RTOL * (np.abs(to_f64(out_f[0])) + np.abs(to_f64(out_c[0]))))
+                     * wabs).sum())
+        _say(f"  L1 loss gpu {loss_g:.6f} oracle {loss_o:.6f} (tolerance {tol:.4f}), bound {eps_o:.4f}")
+        assert abs(loss_g - loss_o) <= tol
+        assert loss_g <= eps_o + tol
+        C = max(float(np.abs(Vd[:, c] @ WO[c]).sum(axis=1).max()) for c in range(h))
+        kept_o = (2 * h * C - eps_o) / (2 * C)
+        sc = res["scores"].view(h, n).double().cpu().numpy()
+        kept_g = float(sc[keep].sum())
+        _say(f"  retained weight gpu {kept_g:.6f} oracle {kept_o:.6f} of {h}")
+        assert abs(kept_g - kept_o) <= 2e-3 * kept_o + 1e-9
+
+
 def decode_sweep_shapes():
     rng = np.random.default_rng(77)
     shapes = []

@@ -8,7 +8,7 @@ from oracle import adakv_oracle as O
 from paper_2407_11550_amd import synth
 
 from parity_util import (assert_end_to_end_close, assert_exact_on_scores, assert_scores_close,
-                         oracle_layer, to_f64)
+                         oracle_batch, oracle_layer, to_f64)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -28,8 +28,12 @@ def _run(wl, q, K, V, **kw):
 def _check_all(wl, q, K, V, out):
     row0 = 0
     soff = 0
+    whole, per_seq = oracle_batch(wl, q, K, V)
+    assert out["scores"].numel() == whole["scores"].size and out["indices"].numel() == whole["indices"].size
+    assert out["cu_seqlens"].numel() == whole["cu_seqlens"].size
+    assert int(out["cu_seqlens"][-1]) == int(whole["cu_seqlens"][-1]) == sum(wl.B)
     for b in range(wl.batch):
-        ref = oracle_layer(wl, q, K, V, b)
+        ref = per_seq[b]
         ns = wl.h_kv * wl.n[b]
         sc = out["scores"][soff:soff + ns].cpu().numpy()
         assert_scores_close(sc, ref["scores"], f"{wl.name} seq {b}")

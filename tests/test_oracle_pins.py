@@ -330,6 +330,103 @@ def test_whole_step_window_one_respects_the_bound_of_theorem_3_1():
         assert loss <= e + 1e-9
 
 
+def test_eviction_loss_and_bound_closed_form():
+    """Eqs. (4)-(6) worked by hand.  Head 0: d_h = 1, q = 1, keys ln 3 and 0 -> A = (3/4, 1/4);
+    values 2 and -4, W^O = (1, -1) -> rows of V W^O are (2, -2) and (-4, 4), absolute row sums
+    4 and 8.  Evicting key 1: y = (1/2, -1/2), y_hat = (2, -2), L1 loss 3; C = 8 (the largest
+    absolute ROW SUM, not the largest element 4); epsilon = 2*1*8 - 2*8*(3/4) = 4.
+    A C taken as the largest element (4), a C taken from V without W^O (4) or a bound without
+    its factor 2 would each give 2: off the value 4, and below the loss itself."""
+    ln3 = math.log(3.0)
+    q = np.array([[1.0]]); K = np.array([[[ln3]], [[0.0]]]); V = np.array([[[2.0]], [[-4.0]]])
+    WO = np.array([[[1.0, -1.0]]])
+    loss, eps = O.eviction_loss_and_bound(q, K, V, WO, np.array([[1, 0]]))
+    assert loss == pytest.approx(3.0, rel=1e-12) and eps == pytest.approx(4.0, rel=1e-12)
+    # nothing evicted: no loss, and the bound is exactly zero (2hC - 2C*h)
+    loss, eps = O.eviction_loss_and_bound(q, K, V, WO, np.array([[1, 1]]))
+    assert loss == pytest.approx(0.0, abs=1e-15) and eps == pytest.approx(0.0, abs=1e-12)
+    # a second head that keeps everything: q = 0 -> A = (1/2, 1/2); values 1 and 3, W^O = (2, 0)
+    # -> rows (2, 0), (6, 0), absolute row sums 2 and 6, so C stays 8 (the maximum over heads).
+    # Retained weight 3/4 + 1; epsilon = 2*2*8 - 2*8*(7/4) = 4; the output difference is head 0's.
+    q2 = np.array([[1.0], [0.0]])
+    K2 = np.array([[[ln3], [5.0]], [[0.0], [-7.0]]])
+    V2 = np.array([[[2.0], [1.0]], [[-4.0], [3.0]]])
+    WO2 = np.array([[[1.0, -1.0]], [[2.0, 0.0]]])
+    loss, eps = O.eviction_loss_and_bound(q2, K2, V2, WO2, np.array([[1, 0], [1, 1]]))
+    assert loss == pytest.approx(3.0, rel=1e-12) and eps == pytest.approx(4.0, rel=1e-12)
+    # with head 1's rows ten times larger C follows them: 60, epsilon = 2*2*60 - 2*60*(7/4) = 30
+    loss, eps = O.eviction_loss_and_bound(q2, K2, V2, WO2 * np.array([1.0, 10.0])[:, None, None],
+                                          np.array([[1, 0], [1, 1]]))
+    assert loss == pytest.approx(3.0, rel=1e-12) and eps == pytest.approx(30.0, rel=1e-12)
+
+
+def test_eviction_loss_is_the_l1_distance_to_library_attention_outputs():
+    """y and y_hat of Eqs. (4)-(5) by another route: torch softmax over all keys, and over the
+    kept keys only (evicted keys removed from the tensors instead of masked), times V W^O."""
+    rng = np.random.default_rng(23)
+    h, d, n, dm = 3, 5, 17, 7
+    q = rng.standard_normal((h, d)); K = rng.standard_normal((n, h, d)); V = rng.standard_normal((n, h, d))
+    WO = rng.standard_normal((h, d, dm))
+    keep = rng.random((h, n)) < 0.5
+    keep[:, 3] = True
+    y = torch.zeros(dm, dtype=torch.float64); y_hat = torch.zeros(dm, dtype=torch.float64)
+    C = 0.0; kept_mass = 0.0
+    for i in range(h):
+        Ki, Vi = torch.tensor(K[:, i]), torch.tensor(V[:, i])
+        A = torch.softmax(Ki @ torch.tensor(q[i]), dim=0)
+        y += A @ Vi @ torch.tensor(WO[i])
+        sel = torch.tensor(np.flatnonzero(keep[i]))
+        A_hat = torch.softmax(Ki[sel] @ torch.tensor(q[i]), dim=0)
+        y_hat += A_hat @ Vi[sel] @ torch.tensor(WO[i])
+        C = max(C, float((Vi @ torch.tensor(WO[i])).abs().sum(dim=1).max()))
+        kept_mass += float(A[sel].sum())
+    loss, eps = O.eviction_loss_and_bound(q, K, V, WO, keep)
+    assert loss == pytest.approx(float((y - y_hat).abs().sum()), rel=1e-10)
+    assert eps == pytest.approx(2 * h * C - 2 * C * kept_mass, rel=1e-10)
+
+
+def test_compress_batch_is_the_sequences_one_by_one_in_the_packed_layout():
+    """The ragged batch: sequence b owns rows tok_off[b] .. of K/V, is compressed on its own
+    (Algorithm 1 acts inside one sequence's layer), and the outputs are laid end to end with
+    cu_seqlens running on.  Offsets are recomputed here by hand; positions stay relative to the
+    sequence; loosely packed sequences (unused rows between them) give the same result."""
+    rng = np.random.default_rng(29)
+    h_q, h, d, w, k = 4, 2, 8, 3, 5
+    n_list, B_list = [40, 7, 23], [2 * (3 + 9), 2 * (3 + 2), 2 * (3 + 23)]
+    gap = 4                                             # unused rows behind every sequence
+    tok_off = [0]
+    for nb in n_list:
+        tok_off.append(tok_off[-1] + nb + w + gap)
+    q = rng.standard_normal((3, h_q, w, d))
+    K = rng.standard_normal((tok_off[-1], h, d)); V = rng.standard_normal((tok_off[-1], h, d))
+    for b in range(3):                                  # poison the unused rows
+        K[tok_off[b] + n_list[b] + w:tok_off[b + 1]] = np.nan
+        V[tok_off[b] + n_list[b] + w:tok_off[b + 1]] = np.nan
+    out = O.compress_batch(q, K, V, n_list, B_list, tok_off, w, k, 0.2)
+    assert out["cu_seqlens"].shape == (3 * h + 1,) and out["cu_seqlens"][0] == 0
+    assert out["cu_seqlens"][-1] == sum(B_list) == len(out["indices"]) == len(out["K_out"])
+    assert len(out["scores"]) == h * sum(n_list) and len(out["budgets"]) == 3 * h
+    row0 = 0; s0 = 0
+    for b in range(3):
+        lo = tok_off[b]
+        one = O.compress_layer(q[b], K[lo:lo + n_list[b] + w], V[lo:lo + n_list[b] + w], n_list[b], w, k,
+                               B_list[b], 0.2)
+        assert np.array_equal(out["scores"][s0:s0 + h * n_list[b]], one["scores"].reshape(-1))
+        assert np.array_equal(out["budgets"][b * h:(b + 1) * h], one["budgets"])
+        assert out["budgets"][b * h:(b + 1) * h].sum() == B_list[b] - w * h
+        assert np.array_equal(out["cu_seqlens"][b * h:(b + 1) * h + 1], one["cu_seqlens"] + row0)
+        idx = out["indices"][row0:row0 + B_list[b]]
+        assert np.array_equal(idx, one["indices"]) and idx.min() >= 0 and idx.max() == n_list[b] + w - 1
+        # the gathered rows, straight from the packed tensors
+        cu = out["cu_seqlens"]
+        for c in range(h):
+            for t in range(cu[b * h + c], cu[b * h + c + 1]):
+                assert np.array_equal(out["K_out"][t], K[lo + out["indices"][t], c])
+                assert np.array_equal(out["V_out"][t], V[lo + out["indices"][t], c])
+        assert not np.isnan(out["K_out"][row0:row0 + B_list[b]]).any()
+        row0 += B_list[b]; s0 += h * n_list[b]
+
+
 def test_compress_layer_invariants_on_a_generated_layer():
     from paper_2407_11550_amd import synth
     wl = synth.workload("tiny")
