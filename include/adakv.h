@@ -280,7 +280,10 @@ int adakv_decode_step(const adakv_layer *L, const void *q_new, const void *k_new
  * the first layers.  ratio = 1 gives avg_budget everywhere.
  *
  *   out (host) [n_layers] int64, written; sum = n_layers * avg_budget, non-increasing
- * Returns ADAKV_EINVAL for n_layers < 1, avg_budget < 0, ratio < 1 or not finite, out == NULL.
+ * The arithmetic is exact (the double `ratio` is taken as the binary fraction it is, everything
+ * else is integer), so out[l] is the floor of the real value in every case.
+ * Returns ADAKV_EINVAL for n_layers < 1, avg_budget < 0, ratio < 1 or not finite, out == NULL;
+ * ADAKV_EUNSUPPORTED for avg_budget > 2^40, n_layers > 2^24 or ratio > 2^20.
  */
 int adakv_pyramid_budgets(int32_t n_layers, int64_t avg_budget, double ratio, int64_t *out);
 

@@ -105,26 +105,31 @@ size_t adakv_workspace_bytes(const adakv_layer *L) {
 
 int adakv_pyramid_budgets(int32_t n_layers, int64_t avg_budget, double ratio, int64_t *out) {
   if (n_layers < 1 || avg_budget < 0 || !(ratio >= 1.0) || isinf(ratio) || !out) return ADAKV_EINVAL;
-  if (avg_budget > (1ll << 40)) return ADAKV_EUNSUPPORTED;       // keeps every product exact in a double
-  const double b_min = 2.0 * (double)avg_budget / (1.0 + ratio);
-  const double b_max = ratio * b_min;
+  if (avg_budget > (1ll << 40) || n_layers > (1 << 24) || ratio > 1048576.0) return ADAKV_EUNSUPPORTED;
+  if (n_layers == 1) { out[0] = avg_budget; return ADAKV_OK; }
+  // Exact integer arithmetic (a product of doubles can land one unit in the last place off an
+  // integer and the floor below would then be wrong by one).  A finite double is p / q with q a
+  // power of two, so with L = n_layers
+  //   real_l = b_max - (b_max - b_min) l / (L-1),  b_min = 2 avg / (1 + r),  b_max = r b_min
+  //          = 2 avg (p (L-1) - (p - q) l) / ((p + q) (L-1)).
+  // p < 2^53, q <= 2^52, avg <= 2^40, L <= 2^24: the numerator stays below 2^119.
+  int e = 0;
+  const double mant = frexp(ratio, &e);                        // ratio = mant * 2^e, 0.5 <= mant < 1
+  unsigned __int128 p = (unsigned __int128)(uint64_t)ldexp(mant, 53), q = 1;   // ratio = p * 2^(e-53)
+  if (e >= 53) p <<= (e - 53); else q <<= (53 - e);
+  while (!(p & 1) && !(q & 1)) { p >>= 1; q >>= 1; }
+  const unsigned __int128 Lm1 = (unsigned __int128)(n_layers - 1);
+  const unsigned __int128 den = (p + q) * Lm1;
   int64_t given = 0;
   for (int32_t l = 0; l < n_layers; ++l) {
-    double real = (double)avg_budget;
-    if (n_layers > 1) real = b_max - (b_max - b_min) * ((double)l / (double)(n_layers - 1));
-    int64_t v = (int64_t)floor(real);
-    if (v < 0) v = 0;
-    if (v > 2 * avg_budget) v = 2 * avg_budget;
-    out[l] = v;
-    given += v;
+    const unsigned __int128 num = (unsigned __int128)(2 * avg_budget) * (p * Lm1 - (p - q) * (unsigned __int128)l);
+    out[l] = (int64_t)(num / den);                             // floor: everything is non-negative
+    given += out[l];
   }
-  // the real values average to avg_budget, so flooring leaves at most n_layers units to hand out
-  // (rounding in the last place may make it one round more or less; the loop copes with both)
+  // the real values sum to exactly L * avg, and every floor lost less than one unit
   int64_t left = (int64_t)n_layers * avg_budget - given;
-  for (int32_t l = 0; left > 0; l = (l + 1) % n_layers, --left) out[l] += 1;
-  for (int32_t l = n_layers - 1; left < 0 && l >= 0; --l)
-    if (out[l] > 0) { out[l] -= 1; ++left; }
-  return ADAKV_OK;
+  for (int32_t l = 0; l < n_layers && left > 0; ++l, --left) out[l] += 1;
+  return left == 0 ? ADAKV_OK : ADAKV_EINVAL;
 }
 
 int adakv_trace_arm(void *const *events, int n_events) {

@@ -492,6 +492,13 @@ def test_pyramid_budgets_c_abi_matches_oracle(lib):
     for L, avg, ratio in [(32, 1024, 4.0), (32, 1000, 2.5), (7, 333, 10.0), (1, 50, 3.0), (2, 5, 9.0),
                           (80, 1024, 1.0), (64, 16384, 20.0), (3, 0, 2.0), (5, 7, 1.5)]:
         assert adakv.pyramid_budgets(L, avg, ratio) == O.pyramid_budgets(L, avg, ratio), (L, avg, ratio)
+    # a grid: every floor must be the exact one (a product of doubles lands an ulp off an integer
+    # in e.g. (15, 2016, 7.0), (8, 7, 1.5), (17, 1024, 2.5))
+    for L in range(1, 41):
+        for avg in (0, 1, 7, 100, 1000, 1024, 2016, 4032, 99991, 1 << 33):
+            for ratio in (1.0, 1.1, 1.5, 2.0, 2.5, 3.3, 7.0, 10.0, 1e3):
+                assert adakv.pyramid_budgets(L, avg, ratio) == O.pyramid_budgets(L, avg, ratio), (L, avg, ratio)
+    assert adakv.pyramid_budgets(15, 2016, 7.0)[0] == 3528           # B_max itself, not one above it
     for bad in [(0, 10, 2.0), (4, -1, 2.0), (4, 10, 0.5), (4, 10, float("inf")), (4, 10, float("nan"))]:
         with pytest.raises(adakv.AdaKVError):
             adakv.pyramid_budgets(*bad)
