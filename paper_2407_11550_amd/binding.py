@@ -117,6 +117,8 @@ class Layer:
         self._off = (ctypes.c_int64 * len(self.tok_off))(*self.tok_off)
         ks = k_strides or (h_kv * d, d)
         vs = v_strides or (h_kv * d, d)
+        self.k_strides, self.v_strides = tuple(int(v) for v in ks), tuple(int(v) for v in vs)
+        self.strides_given = (k_strides is not None, v_strides is not None)
         code = {torch.bfloat16: ADAKV_BF16, torch.float32: ADAKV_FP32, torch.float16: ADAKV_FP16}.get(dtype, 99)
         self.c = _CLayer(code, h_q, h_kv, d, w, pool_k, self.alpha, self.scale, self.batch,
                          self._n, self._B, self._off, ks[0], ks[1], vs[0], vs[1], flags)
@@ -125,6 +127,11 @@ class Layer:
     def from_workload(cls, wl, **kw):
         return cls(wl.dtype, wl.h_q, wl.h_kv, wl.d, wl.w, wl.pool_k, wl.alpha, wl.n, wl.B,
                    tok_off=wl.tok_off, **kw)
+
+    @property
+    def last_token_row(self):
+        """One past the last K/V row any sequence of the layer owns."""
+        return max(self.tok_off[b] + self.n[b] + self.w for b in range(self.batch))
 
     @property
     def num_scores(self):
@@ -153,6 +160,38 @@ def _ptr(t, name, dtype=None):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _need(t, numel, name):
+    """A caller-supplied buffer must hold at least `numel` elements (the kernels index it by the
+    layer's sizes and never look at the tensor)."""
+    if t is not None and t.numel() < numel:
+        raise ValueError(f"{name} holds {t.numel()} elements, the layer needs {numel}")
+
+
+def _check_kv(layer, t, name, strides, given):
+    """K or V must cover every row the layer addresses: element offset of the last one read is
+    (tok_off[-1] - 1) * stride_tok + (h_kv - 1) * stride_head + d - 1.  When the layer was built
+    without explicit strides it assumes a contiguous [tokens, h_kv, d] tensor."""
+    if t is None:
+        return
+    if not given:
+        want = (layer.h_kv * layer.d, layer.d, 1)
+        if t.dim() != 3 or tuple(t.stride()) != want or t.shape[1] != layer.h_kv or t.shape[2] != layer.d:
+            raise ValueError(f"{name} must be a contiguous [tokens, {layer.h_kv}, {layer.d}] tensor "
+                             "(or give the Layer its strides)")
+    rows = layer.last_token_row
+    last = (rows - 1) * strides[0] + (layer.h_kv - 1) * strides[1] + layer.d
+    # a view's reachable extent, from its own shape and strides
+    extent = 1 + sum((sz - 1) * st for sz, st in zip(t.shape, t.stride())) if t.numel() else 0
+    if extent < last:
+        raise ValueError(f"{name} reaches {extent} elements from its first one, the layer addresses {last}")
+
+
+def _check_q(layer, q):
+    if not q.is_contiguous():
+        raise ValueError("q_window must be contiguous")
+    _need(q, layer.batch * layer.h_q * layer.w * layer.d, "q_window")
+
+
 def _stream(stream):
     s = stream if stream is not None else torch.cuda.current_stream()
     return ctypes.c_void_p(s.cuda_stream)
@@ -161,16 +200,20 @@ def _stream(stream):
 def _workspace(layer, ws):
     if ws is None:
         ws = torch.empty(max(workspace_bytes(layer), 16), dtype=torch.uint8, device="cuda")
+    if ws.dtype != torch.uint8:
+        raise ValueError("ws must be a uint8 tensor (its size is taken in bytes)")
     return ws, ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel())
 
 
 def score(layer: Layer, q_window, K, row_lse=None, out=None, ws=None, stream=None):
     """adakv_score: eviction scores [sum_b h_kv*n_b] fp32 (sequence-major, then head)."""
     lib = load_library()
-    if not q_window.is_contiguous():
-        raise ValueError("q_window must be contiguous")
+    _check_q(layer, q_window)
+    _check_kv(layer, K, "K", layer.k_strides, layer.strides_given[0])
+    _need(row_lse, layer.batch * layer.h_q * layer.w, "row_lse")
     if out is None:
         out = torch.empty(layer.num_scores, dtype=torch.float32, device=K.device)
+    _need(out, layer.num_scores, "scores")
     ws, wp, wn = _workspace(layer, ws)
     st = lib.adakv_score(ctypes.byref(layer.c), _ptr(q_window, "q_window", layer.torch_dtype),
                          _ptr(K, "K", layer.torch_dtype), _ptr(row_lse, "row_lse", torch.float32),
@@ -187,6 +230,9 @@ def allocate(layer: Layer, scores, budgets=None, cu_seqlens=None, ws=None, strea
         budgets = torch.empty(layer.num_segments, dtype=torch.int32, device=scores.device)
     if cu_seqlens is None:
         cu_seqlens = torch.empty(layer.num_segments + 1, dtype=torch.int32, device=scores.device)
+    _need(scores, layer.num_scores, "scores")
+    _need(budgets, layer.num_segments, "budgets")
+    _need(cu_seqlens, layer.num_segments + 1, "cu_seqlens")
     ws, wp, wn = _workspace(layer, ws)
     st = lib.adakv_allocate(ctypes.byref(layer.c), _ptr(scores, "scores", torch.float32),
                             _ptr(budgets, "budgets", torch.int32),
@@ -201,6 +247,10 @@ def select(layer: Layer, scores, budgets, cu_seqlens, indices=None, ws=None, str
     lib = load_library()
     if indices is None:
         indices = torch.empty(layer.num_rows_out, dtype=torch.int32, device=scores.device)
+    _need(scores, layer.num_scores, "scores")
+    _need(budgets, layer.num_segments, "budgets")
+    _need(cu_seqlens, layer.num_segments + 1, "cu_seqlens")
+    _need(indices, layer.num_rows_out, "indices")
     ws, wp, wn = _workspace(layer, ws)
     st = lib.adakv_select(ctypes.byref(layer.c), _ptr(scores, "scores", torch.float32),
                           _ptr(budgets, "budgets", torch.int32),
@@ -218,6 +268,12 @@ def compact(layer: Layer, K, V, indices, cu_seqlens, K_out=None, V_out=None, str
         K_out = torch.empty((layer.num_rows_out, layer.d), dtype=layer.torch_dtype, device=K.device)
     if V_out is None:
         V_out = torch.empty((layer.num_rows_out, layer.d), dtype=layer.torch_dtype, device=K.device)
+    _check_kv(layer, K, "K", layer.k_strides, layer.strides_given[0])
+    _check_kv(layer, V, "V", layer.v_strides, layer.strides_given[1])
+    _need(indices, layer.num_rows_out, "indices")
+    _need(cu_seqlens, layer.num_segments + 1, "cu_seqlens")
+    _need(K_out, layer.num_rows_out * layer.d, "K_out")
+    _need(V_out, layer.num_rows_out * layer.d, "V_out")
     st = lib.adakv_compact(ctypes.byref(layer.c), _ptr(K, "K", layer.torch_dtype),
                            _ptr(V, "V", layer.torch_dtype), _ptr(indices, "indices", torch.int32),
                            _ptr(cu_seqlens, "cu_seqlens", torch.int32),
@@ -244,8 +300,10 @@ def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, b
         K_out, V_out = compact(layer, K, V, idx, cu, b.get("K_out"), b.get("V_out"), stream=stream)
         return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
     lib = load_library()
-    if not q_window.is_contiguous():
-        raise ValueError("q_window must be contiguous")
+    _check_q(layer, q_window)
+    _check_kv(layer, K, "K", layer.k_strides, layer.strides_given[0])
+    _check_kv(layer, V, "V", layer.v_strides, layer.strides_given[1])
+    _need(row_lse, layer.batch * layer.h_q * layer.w, "row_lse")
 
     def buf(name, shape, dtype):
         t = b.get(name)
@@ -257,6 +315,12 @@ def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, b
     idx = buf("indices", layer.num_rows_out, torch.int32)
     K_out = buf("K_out", (layer.num_rows_out, layer.d), layer.torch_dtype)
     V_out = buf("V_out", (layer.num_rows_out, layer.d), layer.torch_dtype)
+    for t, numel, name in ((sc, layer.num_scores, "scores"), (bud, layer.num_segments, "budgets"),
+                           (cu, layer.num_segments + 1, "cu_seqlens"), (idx, layer.num_rows_out, "indices"),
+                           (K_out, layer.num_rows_out * layer.d, "K_out"), (V_out, layer.num_rows_out * layer.d, "V_out")):
+        _need(t, numel, name)
+    if ws.numel() < workspace_bytes(layer):
+        raise ValueError(f"ws holds {ws.numel()} bytes, the layer needs {workspace_bytes(layer)}")
     st = lib.adakv_compress(ctypes.byref(layer.c), _ptr(q_window, "q_window", layer.torch_dtype),
                             _ptr(K, "K", layer.torch_dtype), _ptr(V, "V", layer.torch_dtype),
                             _ptr(row_lse, "row_lse", torch.float32), _ptr(sc, "scores", torch.float32),
@@ -312,6 +376,23 @@ def cache_rows(layer: Layer, headroom: int) -> int:
     return layer.num_rows_out + layer.num_segments * int(headroom)
 
 
+def _check_cache(layer, K_cache, V_cache):
+    """The cache tensors are addressed as contiguous rows of d elements."""
+    for t, name in ((K_cache, "K_cache"), (V_cache, "V_cache")):
+        if not t.is_contiguous() or t.shape[-1] != layer.d:
+            raise ValueError(f"{name} must be a contiguous [rows, {layer.d}] tensor")
+
+
+def _check_decode_bufs(layer, headroom, K_cache, V_cache, cu_seqlens, seg_len, out, lse, ws):
+    _check_cache(layer, K_cache, V_cache)
+    _need(cu_seqlens, layer.num_segments + 1, "cu_seqlens")
+    _need(seg_len, layer.num_segments, "seg_len")
+    _need(out, layer.batch * layer.h_q * layer.d, "out")
+    _need(lse, layer.batch * layer.h_q, "lse")
+    if ws.dtype != torch.uint8 or ws.numel() < decode_workspace_bytes(layer, headroom):
+        raise ValueError(f"ws must be a uint8 tensor of at least {decode_workspace_bytes(layer, headroom)} bytes")
+
+
 def decode_workspace_bytes(layer: Layer, headroom: int) -> int:
     return int(load_library().adakv_decode_workspace_bytes(ctypes.byref(layer.c), int(headroom)))
 
@@ -330,6 +411,11 @@ def cache_build(layer: Layer, K, V, indices, cu_seqlens, headroom, K_cache=None,
         seg_len = torch.empty(layer.num_segments, dtype=torch.int32, device=K.device)
     if K_cache.shape[0] < rows or V_cache.shape[0] < rows or seg_len.numel() < layer.num_segments:
         raise ValueError("cache or seg_len too small for this layer and head-room")
+    _check_kv(layer, K, "K", layer.k_strides, layer.strides_given[0])
+    _check_kv(layer, V, "V", layer.v_strides, layer.strides_given[1])
+    _need(indices, layer.num_rows_out, "indices")
+    _need(cu_seqlens, layer.num_segments + 1, "cu_seqlens")
+    _check_cache(layer, K_cache, V_cache)
     st = lib.adakv_cache_build(ctypes.byref(layer.c), _ptr(K, "K", layer.torch_dtype),
                                _ptr(V, "V", layer.torch_dtype), _ptr(indices, "indices", torch.int32),
                                _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(headroom),
@@ -352,6 +438,10 @@ def append(layer: Layer, k_new, v_new, cu_seqlens, headroom, K_cache, V_cache, s
         raise ValueError("k_new and v_new must be contiguous")
     if K_cache.shape[0] < cache_rows(layer, headroom) or V_cache.shape[0] < cache_rows(layer, headroom):
         raise ValueError("cache too small for this layer and head-room")
+    _check_cache(layer, K_cache, V_cache)
+    _need(cu_seqlens, layer.num_segments + 1, "cu_seqlens")
+    _need(seg_len, layer.num_segments, "seg_len")
+    _need(overflow, 1, "overflow")
     st = lib.adakv_append(ctypes.byref(layer.c), _ptr(k_new, "k_new", layer.torch_dtype),
                           _ptr(v_new, "v_new", layer.torch_dtype),
                           _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(headroom),
@@ -380,6 +470,7 @@ def decode_attn(layer: Layer, q_new, cu_seqlens, headroom, K_cache, V_cache, seg
     if ws is None:
         ws = torch.empty(max(decode_workspace_bytes(layer, headroom), 16), dtype=torch.uint8,
                          device=q_new.device)
+    _check_decode_bufs(layer, headroom, K_cache, V_cache, cu_seqlens, seg_len, out, lse, ws)
     st = lib.adakv_decode_attn(ctypes.byref(layer.c), _ptr(q_new, "q_new", layer.torch_dtype),
                                _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(headroom),
                                _ptr(K_cache, "K_cache", layer.torch_dtype),
@@ -412,6 +503,8 @@ def decode_step(layer: Layer, q_new, k_new, v_new, cu_seqlens, headroom, K_cache
     if ws is None:
         ws = torch.empty(max(decode_workspace_bytes(layer, headroom), 16), dtype=torch.uint8,
                          device=q_new.device)
+    _check_decode_bufs(layer, headroom, K_cache, V_cache, cu_seqlens, seg_len, out, lse, ws)
+    _need(overflow, 1, "overflow")
     st = lib.adakv_decode_step(ctypes.byref(layer.c), _ptr(q_new, "q_new", layer.torch_dtype),
                                _ptr(k_new, "k_new", layer.torch_dtype),
                                _ptr(v_new, "v_new", layer.torch_dtype),

@@ -176,3 +176,62 @@ def test_compress_checks_everything_before_launching(lib):
     assert lib.adakv_compress(by, one, one, ctypes.c_void_p(24), None, one, one, one, one, one, one, one, big, None) == -2
     bad = _layer(alpha=2.0)
     assert lib.adakv_compress(ctypes.byref(bad.c), one, one, one, None, one, one, one, one, one, one, one, big, None) == -1
+
+
+def test_binding_rejects_buffers_that_do_not_fit_the_layer(lib):
+    """The kernels index every buffer by the layer's sizes; the binding compares them with the
+    tensors before any pointer reaches the library.  CPU tensors suffice: the size checks come
+    before the device check."""
+    L = _layer(n=[100], B=[8 * 40])
+    bf = torch.bfloat16
+    q = torch.zeros(1, 32, 32, 128, dtype=bf)
+    K = torch.zeros(132, 8, 128, dtype=bf)
+    sc = torch.zeros(800)
+    with pytest.raises(ValueError, match="K reaches"):
+        adakv.score(L, q, K[:131])                                   # one row short of n + w
+    with pytest.raises(ValueError, match="contiguous"):
+        adakv.score(L, q, torch.zeros(132, 8, 144, dtype=bf)[:, :, :128])   # padded rows, strides not declared
+    with pytest.raises(ValueError, match="q_window"):
+        adakv.score(L, q[:, :31], K)
+    with pytest.raises(ValueError, match="q_window must be contiguous"):
+        adakv.score(L, q.transpose(1, 2), K)
+    with pytest.raises(ValueError, match="scores holds 799"):
+        adakv.score(L, q, K, out=torch.zeros(799))
+    with pytest.raises(ValueError, match="row_lse"):
+        adakv.score(L, q, K, row_lse=torch.zeros(32 * 31))
+    with pytest.raises(ValueError, match="budgets"):
+        adakv.allocate(L, sc, budgets=torch.zeros(7, dtype=torch.int32))
+    with pytest.raises(ValueError, match="cu_seqlens"):
+        adakv.allocate(L, sc, cu_seqlens=torch.zeros(8, dtype=torch.int32))
+    with pytest.raises(ValueError, match="scores"):
+        adakv.allocate(L, sc[:-1])
+    i32 = lambda k: torch.zeros(k, dtype=torch.int32)
+    with pytest.raises(ValueError, match="indices"):
+        adakv.select(L, sc, i32(8), i32(9), indices=i32(319))
+    with pytest.raises(ValueError, match="V reaches"):
+        adakv.compact(L, K, K[:100], i32(320), i32(9))
+    with pytest.raises(ValueError, match="K_out"):
+        adakv.compact(L, K, K, i32(320), i32(9), K_out=torch.zeros(319, 128, dtype=bf))
+    with pytest.raises(ValueError, match="ws holds"):
+        adakv.compress(L, q, K, K, ws=torch.zeros(64, dtype=torch.uint8))
+    with pytest.raises(ValueError, match="indices"):
+        adakv.compress(L, q, K, K, ws=torch.zeros(adakv.workspace_bytes(L), dtype=torch.uint8),
+                       bufs=dict(indices=i32(10)))
+    # declared strides: a view into a fused [token][2][head][d] buffer is accepted up to the device check
+    kv = torch.zeros(132, 2, 8, 128, dtype=bf)
+    Ls = _layer(n=[100], B=[8 * 40], k_strides=(2 * 8 * 128, 128), v_strides=(2 * 8 * 128, 128))
+    with pytest.raises(ValueError, match="device tensor"):
+        adakv.compact(Ls, kv[:, 0], kv[:, 1], i32(320), i32(9))
+    with pytest.raises(ValueError, match="K reaches"):
+        adakv.compact(Ls, kv[:131, 0], kv[:, 1], i32(320), i32(9))
+    # a ragged batch: the last sequence's rows count
+    Lb = _layer(n=[50, 60], B=[8 * 40, 8 * 40])
+    with pytest.raises(ValueError, match="K reaches"):
+        adakv.score(Lb, torch.zeros(2, 32, 32, 128, dtype=bf), torch.zeros(50 + 32 + 60 + 31, 8, 128, dtype=bf))
+    # decode side
+    with pytest.raises(ValueError, match="seg_len"):
+        adakv.decode_attn(L, torch.zeros(1, 32, 128, dtype=bf), i32(9), 0, torch.zeros(320, 128, dtype=bf),
+                          torch.zeros(320, 128, dtype=bf), i32(7), ws=torch.zeros(1 << 20, dtype=torch.uint8))
+    with pytest.raises(ValueError, match="ws must be"):
+        adakv.decode_attn(L, torch.zeros(1, 32, 128, dtype=bf), i32(9), 0, torch.zeros(320, 128, dtype=bf),
+                          torch.zeros(320, 128, dtype=bf), i32(8), ws=torch.zeros(8, dtype=torch.uint8))
