@@ -69,6 +69,8 @@ def load_library():
         fn.argtypes = args
     lib.adakv_compress.restype = ctypes.c_int
     lib.adakv_compress.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, Z, V]
+    lib.adakv_compress_static.restype = ctypes.c_int
+    lib.adakv_compress_static.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V]
     I = ctypes.c_int32
     for name, args in (("adakv_cache_build", [P, V, V, V, V, I, V, V, V, V]),
                        ("adakv_append", [P, V, V, V, I, V, V, V, V, V]),
@@ -319,8 +321,8 @@ def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, b
                            (cu, layer.num_segments + 1, "cu_seqlens"), (idx, layer.num_rows_out, "indices"),
                            (K_out, layer.num_rows_out * layer.d, "K_out"), (V_out, layer.num_rows_out * layer.d, "V_out")):
         _need(t, numel, name)
-    if ws.numel() < workspace_bytes(layer):
-        raise ValueError(f"ws holds {ws.numel()} bytes, the layer needs {workspace_bytes(layer)}")
+    if ws.dtype != torch.uint8:                    # its size travels to the library, which checks it
+        raise ValueError("ws must be a uint8 tensor (its size is taken in bytes)")
     st = lib.adakv_compress(ctypes.byref(layer.c), _ptr(q_window, "q_window", layer.torch_dtype),
                             _ptr(K, "K", layer.torch_dtype), _ptr(V, "V", layer.torch_dtype),
                             _ptr(row_lse, "row_lse", torch.float32), _ptr(sc, "scores", torch.float32),
@@ -331,6 +333,42 @@ def compress(layer: Layer, q_window, K, V, row_lse=None, ws=None, stream=None, b
     if st != 0:
         raise AdaKVError(st, "adakv_compress")
     return dict(scores=sc, budgets=bud, cu_seqlens=cu, indices=idx, K_out=K_out, V_out=V_out)
+
+
+STATIC_SCRATCH_BYTES = 24 << 20        # ADAKV_STATIC_SCRATCH_BYTES
+
+
+def compress_static(layer: Layer, q_window, K, V, row_lse=None, stream=None, bufs=None):
+    """adakv_compress_static: the whole step with the library's built-in scratch array instead
+    of a workspace; the C call allocates nothing (outputs not found in `bufs` are made here)."""
+    lib = load_library()
+    b = bufs or {}
+    dev = K.device
+    _check_q(layer, q_window)
+    _check_kv(layer, K, "K", layer.k_strides, layer.strides_given[0])
+    _check_kv(layer, V, "V", layer.v_strides, layer.strides_given[1])
+    _need(row_lse, layer.batch * layer.h_q * layer.w, "row_lse")
+    want = (("scores", layer.num_scores, (layer.num_scores,), torch.float32),
+            ("budgets", layer.num_segments, (layer.num_segments,), torch.int32),
+            ("cu_seqlens", layer.num_segments + 1, (layer.num_segments + 1,), torch.int32),
+            ("indices", layer.num_rows_out, (layer.num_rows_out,), torch.int32),
+            ("K_out", layer.num_rows_out * layer.d, (layer.num_rows_out, layer.d), layer.torch_dtype),
+            ("V_out", layer.num_rows_out * layer.d, (layer.num_rows_out, layer.d), layer.torch_dtype))
+    out = {}
+    for name, numel, shape, dtype in want:
+        t = b.get(name)
+        out[name] = t if t is not None else torch.empty(shape, dtype=dtype, device=dev)
+        _need(out[name], numel, name)
+    st = lib.adakv_compress_static(
+        ctypes.byref(layer.c), _ptr(q_window, "q_window", layer.torch_dtype),
+        _ptr(K, "K", layer.torch_dtype), _ptr(V, "V", layer.torch_dtype),
+        _ptr(row_lse, "row_lse", torch.float32), _ptr(out["scores"], "scores", torch.float32),
+        _ptr(out["budgets"], "budgets", torch.int32), _ptr(out["cu_seqlens"], "cu_seqlens", torch.int32),
+        _ptr(out["indices"], "indices", torch.int32), _ptr(out["K_out"], "K_out", layer.torch_dtype),
+        _ptr(out["V_out"], "V_out", layer.torch_dtype), _stream(stream))
+    if st != 0:
+        raise AdaKVError(st, "adakv_compress_static")
+    return out
 
 
 def pyramid_budgets(n_layers: int, avg_budget: int, ratio: float):
@@ -389,8 +427,8 @@ def _check_decode_bufs(layer, headroom, K_cache, V_cache, cu_seqlens, seg_len, o
     _need(seg_len, layer.num_segments, "seg_len")
     _need(out, layer.batch * layer.h_q * layer.d, "out")
     _need(lse, layer.batch * layer.h_q, "lse")
-    if ws.dtype != torch.uint8 or ws.numel() < decode_workspace_bytes(layer, headroom):
-        raise ValueError(f"ws must be a uint8 tensor of at least {decode_workspace_bytes(layer, headroom)} bytes")
+    if ws.dtype != torch.uint8:                    # its size travels to the library, which checks it
+        raise ValueError("ws must be a uint8 tensor (its size is taken in bytes)")
 
 
 def decode_workspace_bytes(layer: Layer, headroom: int) -> int:

@@ -212,8 +212,8 @@ def test_binding_rejects_buffers_that_do_not_fit_the_layer(lib):
         adakv.compact(L, K, K[:100], i32(320), i32(9))
     with pytest.raises(ValueError, match="K_out"):
         adakv.compact(L, K, K, i32(320), i32(9), K_out=torch.zeros(319, 128, dtype=bf))
-    with pytest.raises(ValueError, match="ws holds"):
-        adakv.compress(L, q, K, K, ws=torch.zeros(64, dtype=torch.uint8))
+    with pytest.raises(ValueError, match="ws must be a uint8"):
+        adakv.compress(L, q, K, K, ws=torch.zeros(1 << 20, dtype=torch.float32))
     with pytest.raises(ValueError, match="indices"):
         adakv.compress(L, q, K, K, ws=torch.zeros(adakv.workspace_bytes(L), dtype=torch.uint8),
                        bufs=dict(indices=i32(10)))
@@ -234,4 +234,4 @@ def test_binding_rejects_buffers_that_do_not_fit_the_layer(lib):
                           torch.zeros(320, 128, dtype=bf), i32(7), ws=torch.zeros(1 << 20, dtype=torch.uint8))
     with pytest.raises(ValueError, match="ws must be"):
         adakv.decode_attn(L, torch.zeros(1, 32, 128, dtype=bf), i32(9), 0, torch.zeros(320, 128, dtype=bf),
-                          torch.zeros(320, 128, dtype=bf), i32(8), ws=torch.zeros(8, dtype=torch.uint8))
+                          torch.zeros(320, 128, dtype=bf), i32(8), ws=torch.zeros(1 << 18, dtype=torch.int32))
