@@ -53,7 +53,9 @@ typedef enum {
   ADAKV_EINVAL = -1,       /* NULL required pointer, or a parameter outside its domain      */
   ADAKV_EUNSUPPORTED = -2, /* valid problem, but a shape/dtype this build has no kernel for  */
   ADAKV_EWORKSPACE = -3,   /* ws == NULL or ws_bytes < adakv_workspace_bytes(L)              */
-  ADAKV_EHIP = -4          /* a HIP runtime call failed (kernel launch)                      */
+  ADAKV_EHIP = -4,         /* a HIP runtime call failed (kernel launch)                      */
+  ADAKV_ESCRATCH = -5      /* adakv_compress_static: the layer needs more scratch memory than
+                              the library's built-in array holds (ADAKV_STATIC_SCRATCH_BYTES)  */
 } adakv_status;
 
 #define ADAKV_MAX_BATCH 64          /* sequences per call                                    */
@@ -188,6 +190,27 @@ int adakv_compress(const adakv_layer *L, const void *q_window, const void *K, co
                    const float *row_lse, float *scores, int32_t *budgets, int32_t *cu_seqlens,
                    int32_t *indices, void *K_out, void *V_out, void *ws, size_t ws_bytes,
                    void *hip_stream);
+
+/*
+ * adakv_compress for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments minus `ws`, same kernels, same results bit for bit; the scratch memory is a
+ * built-in device array of ADAKV_STATIC_SCRATCH_BYTES that lives in the library's code object
+ * (every GPU the library runs on holds its own copy until the process ends).  The call allocates
+ * and frees nothing; the first call on a device looks the array's address up once.
+ *
+ *   - the HIP device current at the call must be the one `hip_stream` and all buffers belong to
+ *   - a layer with adakv_workspace_bytes(L) > ADAKV_STATIC_SCRATCH_BYTES is rejected with
+ *     ADAKV_ESCRATCH before anything is launched (every named workload of this build fits)
+ *   - all calls on one GPU share the one array: it keeps the previous call's contents (the
+ *     kernels clear what they need cleared), and two calls that overlap on one GPU (different
+ *     streams or threads) race on it.  Order them on one stream.
+ */
+#define ADAKV_STATIC_SCRATCH_BYTES (24u << 20)
+int adakv_compress_static(const adakv_layer *L, const void *q_window, const void *K, const void *V,
+                          const float *row_lse, float *scores, int32_t *budgets,
+                          int32_t *cu_seqlens, int32_t *indices, void *K_out, void *V_out,
+                          void *hip_stream);
 
 /*
  * ---- Decode side of the flattened layout (Section 3.5; Section 3.1, Eqs. 1-2) --------------

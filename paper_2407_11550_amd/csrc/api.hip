@@ -3,6 +3,8 @@
 #include <math.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace adakv {
@@ -93,6 +95,29 @@ bool trace_pair(const char *name, hipEvent_t *start, hipEvent_t *stop) {
 
 }  // namespace adakv
 
+// Scratch for adakv_compress_static.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address differs per GPU and is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[ADAKV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (nullptr if HIP refuses).
+void *static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
 using namespace adakv;
 
 extern "C" {
@@ -158,6 +183,7 @@ const char *adakv_strerror(int status) {
     case ADAKV_EUNSUPPORTED: return "shape, dtype or alignment not supported by this build";
     case ADAKV_EWORKSPACE: return "workspace missing or smaller than adakv_workspace_bytes";
     case ADAKV_EHIP: return "a HIP runtime call failed";
+    case ADAKV_ESCRATCH: return "the layer needs more scratch memory than the built-in array of adakv_compress_static holds";
     default: return "unknown status";
   }
 }
@@ -248,6 +274,21 @@ int adakv_compress(const adakv_layer *L, const void *q_window, const void *K, co
   if ((rc = adakv_allocate(&P, scores, budgets, cu_seqlens, ws, ws_bytes, hip_stream)) != ADAKV_OK) return rc;
   if ((rc = adakv_select(&P, scores, budgets, cu_seqlens, indices, ws, ws_bytes, hip_stream)) != ADAKV_OK) return rc;
   return adakv_compact(&P, K, V, indices, cu_seqlens, K_out, V_out, hip_stream);
+}
+
+// ---- the whole step without a workspace argument ------------------------------------------------
+int adakv_compress_static(const adakv_layer *L, const void *q_window, const void *K, const void *V,
+                          const float *row_lse, float *scores, int32_t *budgets,
+                          int32_t *cu_seqlens, int32_t *indices, void *K_out, void *V_out,
+                          void *hip_stream) {
+  SeqTab st; Dims dm;
+  int rc = build_tables(L, st, dm);
+  if (rc != ADAKV_OK) return rc;
+  if (workspace_for(st, dm, L->dtype) > (size_t)ADAKV_STATIC_SCRATCH_BYTES) return ADAKV_ESCRATCH;
+  void *ws = static_scratch();
+  if (!ws) return ADAKV_EHIP;
+  return adakv_compress(L, q_window, K, V, row_lse, scores, budgets, cu_seqlens, indices, K_out,
+                        V_out, ws, ADAKV_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 // ---- decode side ------------------------------------------------------------------------------
