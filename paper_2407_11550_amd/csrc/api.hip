@@ -64,13 +64,13 @@ static int build_tables(const adakv_layer *L, SeqTab &st, Dims &dm) {
 
 // Workspace: the scoring part first, the Top-k part behind it (they must not overlap: in
 // pipeline mode the scoring call already writes into the Top-k part).
-static size_t topk_offset(const SeqTab &st, const Dims &dm, int dtype) {
-  return align_up(plan_score(st, dm, dtype).total, 256);
-}
-static size_t workspace_for(const SeqTab &st, const Dims &dm, int dtype) {
-  return topk_offset(st, dm, dtype) + plan_topk_bytes(st, dm) + 256;
-}
 static bool pool_first(const adakv_layer *L) { return (L->flags & ADAKV_FLAG_POOL_THEN_MEAN) != 0; }
+static size_t topk_offset(const SeqTab &st, const Dims &dm, const adakv_layer *L) {
+  return align_up(plan_score(st, dm, L->dtype, pool_first(L)).total, 256);
+}
+static size_t workspace_for(const SeqTab &st, const Dims &dm, const adakv_layer *L) {
+  return topk_offset(st, dm, L) + plan_topk_bytes(st, dm) + 256;
+}
 static bool pipeline_mode(const adakv_layer *L, const Dims &dm) {
   return (L->flags & ADAKV_FLAG_PIPELINE) != 0 && carry_supported(dm, L->dtype) && !pool_first(L);
 }
@@ -125,7 +125,7 @@ extern "C" {
 size_t adakv_workspace_bytes(const adakv_layer *L) {
   SeqTab st; Dims dm;
   if (build_tables(L, st, dm) != ADAKV_OK) return 0;
-  return workspace_for(st, dm, L->dtype);
+  return workspace_for(st, dm, L);
 }
 
 int adakv_pyramid_budgets(int32_t n_layers, int64_t avg_budget, double ratio, int64_t *out) {
@@ -195,13 +195,13 @@ int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const
   if (rc != ADAKV_OK) return rc;
   if (!q_window || !K || !scores) return ADAKV_EINVAL;
   if (!aligned16(q_window) || !aligned16(K) || !aligned16(scores)) return ADAKV_EUNSUPPORTED;
-  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  if (!ws || ws_bytes < workspace_for(st, dm, L)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
-  ScorePlan pl = plan_score(st, dm, L->dtype);
+  ScorePlan pl = plan_score(st, dm, L->dtype, pool_first(L));
   hipStream_t s = (hipStream_t)hip_stream;
   if (pool_first(L) && dm.pool_k / 2 > 100) return ADAKV_EUNSUPPORTED;
   TopkCarry tc = {nullptr, 0u, nullptr, nullptr};
-  if (pipeline_mode(L, dm)) tc = plan_carry(st, dm, wsp + topk_offset(st, dm, L->dtype));
+  if (pipeline_mode(L, dm)) tc = plan_carry(st, dm, wsp + topk_offset(st, dm, L));
   hipError_t e = (mfma_path_supported(dm, L->dtype) && !pool_first(L))
                      ? launch_score_mfma(st, dm, L->dtype, q_window, K, row_lse, scores, wsp, pl, tc, s)
                      : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
@@ -216,10 +216,10 @@ int adakv_allocate(const adakv_layer *L, const float *scores, int32_t *budgets,
   if (rc != ADAKV_OK) return rc;
   if (!scores || !budgets || !cu_seqlens) return ADAKV_EINVAL;
   if (!aligned16(scores)) return ADAKV_EUNSUPPORTED;
-  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  if (!ws || ws_bytes < workspace_for(st, dm, L)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   hipError_t e = launch_allocate(st, dm, scores, budgets, cu_seqlens,
-                                 wsp + topk_offset(st, dm, L->dtype), pipeline_mode(L, dm),
+                                 wsp + topk_offset(st, dm, L), pipeline_mode(L, dm),
                                  (hipStream_t)hip_stream);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
@@ -232,10 +232,10 @@ int adakv_select(const adakv_layer *L, const float *scores, const int32_t *budge
   if (rc != ADAKV_OK) return rc;
   if (!scores || !budgets || !cu_seqlens || !indices) return ADAKV_EINVAL;
   if (!aligned16(scores)) return ADAKV_EUNSUPPORTED;
-  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  if (!ws || ws_bytes < workspace_for(st, dm, L)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
   hipError_t e = launch_select(st, dm, scores, budgets, cu_seqlens, indices,
-                               wsp + topk_offset(st, dm, L->dtype), pipeline_mode(L, dm),
+                               wsp + topk_offset(st, dm, L), pipeline_mode(L, dm),
                                (hipStream_t)hip_stream);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
 }
@@ -267,7 +267,7 @@ int adakv_compress(const adakv_layer *L, const void *q_window, const void *K, co
       !aligned16(K_out) || !aligned16(V_out))
     return ADAKV_EUNSUPPORTED;
   if (pool_first(L) && dm.pool_k / 2 > 100) return ADAKV_EUNSUPPORTED;
-  if (!ws || ws_bytes < workspace_for(st, dm, L->dtype)) return ADAKV_EWORKSPACE;
+  if (!ws || ws_bytes < workspace_for(st, dm, L)) return ADAKV_EWORKSPACE;
   adakv_layer P = *L;
   P.flags |= ADAKV_FLAG_PIPELINE;
   if ((rc = adakv_score(&P, q_window, K, row_lse, scores, ws, ws_bytes, hip_stream)) != ADAKV_OK) return rc;
@@ -284,7 +284,7 @@ int adakv_compress_static(const adakv_layer *L, const void *q_window, const void
   SeqTab st; Dims dm;
   int rc = build_tables(L, st, dm);
   if (rc != ADAKV_OK) return rc;
-  if (workspace_for(st, dm, L->dtype) > (size_t)ADAKV_STATIC_SCRATCH_BYTES) return ADAKV_ESCRATCH;
+  if (workspace_for(st, dm, L) > (size_t)ADAKV_STATIC_SCRATCH_BYTES) return ADAKV_ESCRATCH;
   void *ws = static_scratch();
   if (!ws) return ADAKV_EHIP;
   return adakv_compress(L, q_window, K, V, row_lse, scores, budgets, cu_seqlens, indices, K_out,

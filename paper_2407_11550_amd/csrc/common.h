@@ -73,7 +73,7 @@ struct ScorePlan {                  // byte offsets into the workspace
   size_t total;
   int part_chunk;                   // keys per partial-statistics chunk
 };
-ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype);
+ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype, bool pool_first);
 bool mfma_path_supported(const Dims &dm, int dtype);
 
 hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, const void *q,

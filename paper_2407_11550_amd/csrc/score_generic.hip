@@ -267,17 +267,19 @@ __global__ __launch_bounds__(256) void pool_kernel(SeqTab st, ChunkTab ct, int p
   scores[base + j] = m;
 }
 
-ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype) {
+ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype, bool pool_first) {
   ScorePlan p;
-  p.part_chunk = GEN_CHUNK;   // both paths size their partial statistics for the smaller chunk
-  const size_t chunks = make_chunks(st, GEN_CHUNK).off[st.batch];
+  // partial statistics: one (max, sum) pair per window row and chunk of keys; the plain-FMA
+  // kernels cut a sequence into GEN_CHUNK keys, the matrix-core kernels into longer chunks
+  const bool mfma = mfma_path_supported(dm, dtype) && !pool_first;
+  p.part_chunk = mfma ? choose_mfma_variant(st, dm).chunk : GEN_CHUNK;
+  const size_t chunks = make_chunks(st, p.part_chunk).off[st.batch];
   const size_t RQ = (size_t)dm.h_q * dm.w;
   size_t o = 0;
   p.part = o; o += align_up(chunks * RQ * 8, 256);
   p.lse = o; o += align_up((size_t)st.batch * RQ * 4, 256);
   p.raw = o; o += align_up((size_t)st.score_off[st.batch] * 4, 256);
   p.total = o;
-  (void)dtype;
   return p;
 }
 

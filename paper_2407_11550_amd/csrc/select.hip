@@ -6,81 +6,82 @@
 // Ties are decided by position (lower flat index first) through counts and prefix sums; the
 // order in which atomics land never reaches a result, so every output is deterministic.
 //
-// A score becomes a 32-bit key whose unsigned order is the float order.  Three passes over the
-// scores take the key's bits 31..21, 20..10, 9..0; each pass histograms the digit of the
-// elements that still match the digits chosen so far.
+// A score becomes a 32-bit key whose unsigned order is the float order; its digits are the
+// key's bits 31..21, 20..10 and 9..0.  Each scope runs two kernels (a kernel boundary is the
+// cheapest device-wide synchronisation on this part; a device-scope fence inside a kernel writes
+// a whole L2 back), so the whole Top-k is four launches after the first-digit histograms, which
+// the scoring kernel leaves behind in pipeline mode (two small kernels make them otherwise):
 //
-// Blocks of one kernel never talk to each other: integer atomics add the per-block counts into
-// global histograms, and the digit that holds the k-th largest element is found by the NEXT
-// kernel, whose every block scans the (small) finished histogram in its prologue.  A kernel
-// boundary is the cheapest device-wide synchronisation on this part: a device-scope fence
-// inside a kernel writes a whole L2 back.
+//   gather   every block of 4096 positions finds the first digit d0 of its scope's threshold from
+//            the finished first-digit histogram, adds the second digits of its elements under d0
+//            to the scope's second-digit histogram, and leaves these elements behind sorted by
+//            second digit (a counting sort inside the block: bucket starts + entries), together
+//            with the number of its elements above d0;
+//   finish / emit
+//            finds the second digit d1 from the finished histogram.  The elements that share
+//            the threshold's 22-bit prefix are then the bucket d1 of every block: few, and
+//            found through the bucket starts without touching the scores again.  The last digit
+//            and the number of ties to take come from them inside the block.  The layer scope
+//            then counts per head and applies the safeguard; the head scope places every kept
+//            position by prefix counts (earlier blocks' counts from the bucket starts, then a
+//            block scan over 16 consecutive positions per thread).
 //
-// Kernels per call: [clear, pass 0,] pass 1, pass 2, then alloc_finish (layer scope) or
-// emit_write (head scope).  The bracketed two are skipped in pipeline mode, where the scoring
-// kernels have cleared the histograms and counted the first digits (which do not depend on the
-// scope).  The last pass also leaves per-block counts behind (elements above the threshold's
-// 22-bit prefix; head scope: the block's own last-digit histogram), so that the kernel after it
-// does not have to read the scores once more just to count.
+// When more elements share a 22-bit prefix than a block can hold at once (plateaus: equal or
+// almost equal scores), the finishing kernels stream the buckets instead of holding them.
 #include "common.h"
 
 namespace adakv {
 
 namespace {
 
+constexpr int ENT_PER_BLOCK = SEL_CHUNK;       // a block's elements under d0: at most all of them
+constexpr int HOLD_LAYER = 4096;               // prefix-sharing elements the finishing kernel keeps in LDS
+constexpr int HOLD_HEAD = 2048;                // the same for an emit block
+constexpr int SERIAL_MAX = 64;                 // longest bucket a single thread copies by itself
+
 struct TopkWs {             // byte offsets inside the Top-k part of the workspace
-  size_t hist;              // u32 [3][batch*h][RADIX_BINS]  per-head digit counts, layer scope
-  size_t hist_tot;          // u32 [3][batch][RADIX_BINS]    the same summed over heads
-  size_t hist_sel;          // u32 [3][batch*h][RADIX_BINS]  per-head digit counts, head scope
+  size_t hist0;             // u32 [batch*h][RADIX_BINS]  first digits per head
+  size_t hist_tot0;         // u32 [batch][RADIX_BINS]    first digits per sequence
+  size_t hist1_tot;         // u32 [batch][RADIX_BINS]    layer scope: second digits under the sequence's d0
+  size_t hist1;             // u32 [batch*h][RADIX_BINS]  head scope: second digits under the head's d0
   size_t zero_end;          // everything before this starts at zero
-  size_t state;             // uint2 [2][batch*h]: (digits chosen, rank left) after passes 0 and 1
-  size_t chunk_hist;        // u16 [chunks][h][1024]  head scope, last pass: each block's own digit counts
-  size_t chunk_sure;        // i32 [chunks][h]        last pass of either scope: the block's elements above
-                            //                        the threshold's 22-bit prefix
-  size_t total;
+  size_t starts;            // u16 [blocks][RADIX_BINS]   bucket starts of a block's sorted entries
+  size_t note;              // BlockNote [blocks]
+  size_t entries;           // u16 [blocks][SEL_CHUNK]    last digits of a block's elements under d0, by bucket
+  size_t bytes;
+};
+
+struct BlockNote {          // per gather block
+  int entries;              // elements under d0 (= end of the last bucket)
+  int above;                // elements above d0
 };
 
 TopkWs plan(const SeqTab &st, const Dims &dm) {
   TopkWs p;
   const size_t nseg = (size_t)st.batch * dm.h_kv;
   size_t o = 0;
-  p.hist = o; o += 3 * nseg * RADIX_BINS * 4;
-  p.hist_tot = o; o += 3 * (size_t)st.batch * RADIX_BINS * 4;
-  p.hist_sel = o; o += 3 * nseg * RADIX_BINS * 4;
+  p.hist0 = o; o += nseg * RADIX_BINS * 4;
+  p.hist_tot0 = o; o += (size_t)st.batch * RADIX_BINS * 4;
+  p.hist1_tot = o; o += (size_t)st.batch * RADIX_BINS * 4;
+  p.hist1 = o; o += nseg * RADIX_BINS * 4;
   p.zero_end = o;
-  p.state = o; o += align_up(2 * nseg * 8, 256);
   const size_t blocks = (size_t)make_chunks(st, SEL_CHUNK).off[st.batch] * dm.h_kv;
-  p.chunk_hist = o; o += align_up(blocks * 1024 * 2, 256);
-  p.chunk_sure = o; o += align_up(blocks * 4, 256);
-  p.total = o;
+  p.starts = o; o += align_up(blocks * RADIX_BINS * 2, 256);
+  p.note = o; o += align_up(blocks * sizeof(BlockNote), 256);
+  p.entries = o; o += align_up(blocks * ENT_PER_BLOCK * 2, 256);
+  p.bytes = o;
   return p;
 }
 
-// The per-head histograms of the three passes of one scope.  The first digit of a score does not
-// depend on the scope, so in pipeline mode the head scope reads the layer scope's pass-0 counts.
-struct HistSet {
-  unsigned *p[3];           // each [batch*h][RADIX_BINS]
-};
-
-template <int P> __device__ __forceinline__ bool matches(unsigned key, unsigned prefix) {
-  if (P == 0) return true;
-  if (P == 1) return (key >> 21) == (prefix >> 21);
-  return (key >> 10) == (prefix >> 10);
-}
-template <int P> __device__ __forceinline__ unsigned digit_of(unsigned key) {
-  if (P == 0) return key >> 21;
-  if (P == 1) return (key >> 10) & 2047u;
-  return key & 1023u;
-}
-template <int P> __device__ __forceinline__ unsigned with_digit(unsigned prefix, unsigned dgt) {
-  if (P == 0) return dgt << 21;
-  if (P == 1) return (prefix & 0xFFE00000u) | (dgt << 10);
-  return (prefix & 0xFFFFFC00u) | dgt;
-}
-
-struct Rank {
-  unsigned prefix;   // digits chosen so far, in key position
-  int krem;          // rank of the threshold among the elements matching them; 0 = select nothing
+// What the kernels of one scope share.
+struct TopkBufs {
+  const unsigned *hist0;     // first digits: per head
+  const unsigned *hist_tot0; // first digits: per sequence
+  unsigned *hist1;           // head scope: second digits under the head's d0
+  unsigned *hist1_tot;       // layer scope: second digits under the sequence's d0
+  unsigned short *starts;
+  BlockNote *note;
+  unsigned short *entries;   // last digits (10 bits each)
 };
 
 // This thread's NB/256 consecutive bins of a finished histogram, as 16-byte loads.  Kept apart
@@ -102,10 +103,11 @@ template <int NB> __device__ __forceinline__ Bins<NB> load_bins(const unsigned *
   return r;
 }
 
-// All threads of a block (the first 256 hold the bins): given the finished histogram of a pass (NB bins, this thread's part
-// in `mine`) and the rank krem >= 1 among the elements it counts, find the digit whose bin holds
-// that rank, counting from the largest digit down.  Returns the digit and the rank inside its
-// bin (>= 1).
+// All threads of a block (the first 256 hold the bins): given a finished histogram (NB bins, this
+// thread's part in `mine`) and the rank krem >= 1 among the elements it counts, find the digit
+// whose bin holds that rank, counting from the largest digit down.  Returns the digit and the
+// rank inside its bin (>= 1).  A rank beyond the histogram's total gives digit 0 and the rank
+// unchanged (callers clamp what they derive from it).
 template <int NB>
 __device__ __forceinline__ void locate(const Bins<NB> &mine, int krem, unsigned &digit,
                                        int &rank_in_bin, unsigned *sh /*[8]*/) {
@@ -126,7 +128,7 @@ __device__ __forceinline__ void locate(const Bins<NB> &mine, int krem, unsigned 
   __syncthreads();
   unsigned above = suf - s;                            // elements in bins owned by higher threads
   for (int i = wv + 1; i < 4; ++i) above += sh[i];
-  if (above < (unsigned)krem && (unsigned)krem <= above + s) {
+  if (tid < 256 && above < (unsigned)krem && (unsigned)krem <= above + s) {
     unsigned acc = above;
 #pragma unroll
     for (int i = PER - 1; i >= 0; --i) {
@@ -148,64 +150,47 @@ __global__ __launch_bounds__(256) void topk_init_kernel(unsigned *__restrict__ z
   for (size_t i = i0; i < zero_words; i += (size_t)gridDim.x * blockDim.x) zero_begin[i] = 0u;
 }
 
-// Rank state in front of pass P for scope segment S: pass 0 starts from k; later passes take the
-// stored state of the pass before the previous one and scan the previous pass's histogram.
-template <int P, bool LAYER>
-__device__ __forceinline__ Rank rank_before_pass(const SeqTab &st, int h, int b, int c,
-                                                 const int *__restrict__ budgets,
-                                                 const HistSet &hist,
-                                                 const unsigned *__restrict__ hist_tot,
-                                                 const uint2 *__restrict__ state, unsigned *sh) {
-  const int nsegs = st.batch * h;
-  const int S = LAYER ? b : b * h + c;
-  Rank r;
-  r.prefix = 0u;
-  r.krem = 0;
-  if (P == 0) {
-    r.krem = LAYER ? st.Bp[b] : budgets[b * h + c];
-    return r;
-  } else {
-    constexpr int Q = P - 1;                           // the pass whose histogram is scanned
-    constexpr int NBQ = (Q == 2) ? 1024 : RADIX_BINS;
-    const unsigned *bins = LAYER ? hist_tot + ((size_t)Q * st.batch + b) * RADIX_BINS
-                                 : hist.p[Q] + (size_t)(b * h + c) * RADIX_BINS;
-    // the histogram and the stored state do not depend on each other: both loads go out now
-    const Bins<NBQ> mine = load_bins<NBQ>(bins);
-    if (P == 1) {
-      r.krem = LAYER ? st.Bp[b] : budgets[b * h + c];
-    } else {
-      const uint2 v = state[(size_t)(P - 2) * nsegs + S];
-      r.prefix = v.x;
-      r.krem = (int)v.y;
+// First digits of every score, per head and per sequence (outside pipeline mode, where the
+// scoring kernel counts them).  grid.x runs over the SEL_CHUNK-sized chunks of all sequences,
+// grid.y over heads.
+__global__ __launch_bounds__(256) void topk_digit0_kernel(SeqTab st, ChunkTab ct, int h,
+                                                          const float *__restrict__ scores,
+                                                          unsigned *__restrict__ hist0,
+                                                          unsigned *__restrict__ hist_tot0) {
+  __shared__ unsigned lh[RADIX_BINS];
+  const int tid = threadIdx.x;
+  const int b = find_seq(ct, st.batch, blockIdx.x);
+  const int n = st.n[b];
+  const int chunk = blockIdx.x - ct.off[b];
+  const int c = blockIdx.y;
+  const float *row = scores + st.score_off[b] + (size_t)c * n;
+  const int j0 = chunk * SEL_CHUNK, j1 = min(n, j0 + SEL_CHUNK);
+  for (int i = tid; i < RADIX_BINS; i += 256) lh[i] = 0u;
+  __syncthreads();
+  for (int j = j0 + tid; j < j1; j += 256) atomicAdd(&lh[key_of(row[j]) >> 21], 1u);
+  __syncthreads();
+  unsigned *gh = hist0 + (size_t)(b * h + c) * RADIX_BINS;
+  unsigned *gt = hist_tot0 + (size_t)b * RADIX_BINS;
+  for (int i = tid; i < RADIX_BINS; i += 256) {
+    const unsigned v = lh[i];
+    if (v) {
+      atomicAdd(&gh[i], v);
+      atomicAdd(&gt[i], v);
     }
-    if (r.krem <= 0) return r;
-    unsigned digit;
-    int rank;
-    locate<NBQ>(mine, r.krem, digit, rank, sh);
-    r.prefix = with_digit<Q>(r.prefix, digit);
-    r.krem = rank;
-    return r;
   }
 }
 
-// One histogram pass.  grid.x runs over the SEL_CHUNK-sized chunks of all sequences, grid.y over
-// heads.  LAYER: the k-th largest is sought over all heads of a sequence.
-template <int P, bool LAYER>
-__global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, int h,
-                                                        const float *__restrict__ scores,
-                                                        const int *__restrict__ budgets,
-                                                        HistSet hist,
-                                                        unsigned *__restrict__ hist_tot,
-                                                        uint2 *__restrict__ state,
-                                                        unsigned short *__restrict__ chunk_hist,
-                                                        int *__restrict__ chunk_sure) {
-  constexpr int NB = (P == 2) ? 1024 : RADIX_BINS;
-  constexpr bool LAST_HEAD_PASS = (P == 2) && !LAYER;   // also leaves what the emit kernel counts with
-  constexpr bool LAST_LAYER_PASS = (P == 2) && LAYER;   // also counts what lies above the last bucket
-  __shared__ unsigned lh[RADIX_BINS];
+// The gather kernel of either scope.  grid as above.  LAYER: the threshold is sought over all
+// heads of a sequence (rank B'), else inside the block's own head (rank budgets[segment]).
+template <bool LAYER>
+__global__ __launch_bounds__(256) void topk_gather_kernel(SeqTab st, ChunkTab ct, int h,
+                                                          const float *__restrict__ scores,
+                                                          const int *__restrict__ budgets,
+                                                          TopkBufs tb) {
+  __shared__ unsigned lh[RADIX_BINS];                  // second-digit counts, then running bucket fill
   __shared__ unsigned sh[8];
-  __shared__ int sh_sure;
-  const int tid = threadIdx.x;
+  __shared__ int sh_above, sh_wave[4];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int b = find_seq(ct, st.batch, blockIdx.x);
   // the first sequence's facts sit at fixed places of the kernel arguments and arrive with the
   // first scalar fetch; only later sequences of a batch cost a dependent one
@@ -213,9 +198,10 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
   if (b != 0) { n = st.n[b]; cfirst = ct.off[b]; soff = st.score_off[b]; }
   const int chunk = blockIdx.x - cfirst;
   const int c = blockIdx.y;
-  const int nsegs = st.batch * h;
+  const int seg = b * h + c;
+  const size_t blk = (size_t)blockIdx.x * h + c;
   // the block's scores are requested first, so they arrive while the prologue below waits for
-  // the previous pass's histogram (indices past the end are clamped, the values ignored)
+  // the histogram (indices past the end are clamped, the values ignored)
   const float *row = scores + soff + (size_t)c * n;
   const int j0 = chunk * SEL_CHUNK;
   const int j1 = min(n, j0 + SEL_CHUNK);
@@ -223,104 +209,213 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(SeqTab st, ChunkTab ct, 
   float sc[EPB];
 #pragma unroll
   for (int i = 0; i < EPB; ++i) sc[i] = row[min(j0 + tid + 256 * i, j1 - 1)];
-  for (int i = tid; i < NB; i += 256) lh[i] = 0u;
-  if (P == 2 && tid == 0) sh_sure = 0;
-  const Rank r = rank_before_pass<P, LAYER>(st, h, b, c, budgets, hist, hist_tot, state, sh);
-  if (P >= 1 && chunk == 0 && (!LAYER || c == 0) && tid == 0)
-    state[(size_t)(P - 1) * nsegs + (LAYER ? b : b * h + c)] = make_uint2(r.prefix, (unsigned)r.krem);
-  __syncthreads();
-  if (r.krem <= 0) return;                             // nothing to select in this segment
-  int sure = 0;
+  const Bins<RADIX_BINS> mine = load_bins<RADIX_BINS>(
+      LAYER ? tb.hist_tot0 + (size_t)b * RADIX_BINS : tb.hist0 + (size_t)seg * RADIX_BINS);
+  const int krem = LAYER ? st.Bp[b] : budgets[seg];
+  for (int i = tid; i < RADIX_BINS; i += 256) lh[i] = 0u;
+  if (tid == 0) sh_above = 0;
+  if (krem <= 0) {                                     // nothing to select in this scope
+    if (tid == 0) { tb.note[blk].entries = 0; tb.note[blk].above = 0; }
+    return;
+  }
+  unsigned d0;
+  int r0;
+  locate<RADIX_BINS>(mine, krem, d0, r0, sh);          // its barriers also publish the cleared lh
+  unsigned keys[EPB];
+  int above = 0;
 #pragma unroll
   for (int i = 0; i < EPB; ++i) {
-    const unsigned key = key_of(sc[i]);
     const bool in = j0 + tid + 256 * i < j1;
-    if (in && matches<P>(key, r.prefix)) atomicAdd(&lh[digit_of<P>(key)], 1u);
-    if (P == 2) sure += in && (key >> 10) > (r.prefix >> 10);
+    const unsigned key = key_of(sc[i]);
+    keys[i] = key;
+    const unsigned dg = key >> 21;
+    if (in && dg == d0) atomicAdd(&lh[(key >> 10) & 2047u], 1u);
+    above += in && dg > d0;
   }
-  if (P == 2) {
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) sure += __shfl_xor(sure, off);
-    if ((tid & 63) == 0) atomicAdd(&sh_sure, sure);
+  for (int off = 32; off > 0; off >>= 1) above += __shfl_xor(above, off);
+  if (lane == 0) atomicAdd(&sh_above, above);
+  __syncthreads();
+  // bucket starts, largest digit first is not needed: buckets are addressed by digit.  Thread t
+  // owns bins 8t .. 8t+7: exclusive scan over the block.
+  unsigned cnt[8];
+  unsigned tsum = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { cnt[i] = lh[tid * 8 + i]; tsum += cnt[i]; }
+  unsigned inc = tsum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned v = __shfl_up(inc, off);
+    if (lane >= off) inc += v;
+  }
+  if (lane == 63) sh_wave[wv] = (int)inc;
+  __syncthreads();
+  unsigned base = inc - tsum;
+  for (int i = 0; i < wv; ++i) base += (unsigned)sh_wave[i];
+  // starts to memory (one 16-byte store), counts to the scope's histograms, starts into lh
+  unsigned stt[8];
+  unsigned run = base;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { stt[i] = run; run += cnt[i]; }
+  uint4 packed;
+  packed.x = stt[0] | (stt[1] << 16); packed.y = stt[2] | (stt[3] << 16);
+  packed.z = stt[4] | (stt[5] << 16); packed.w = stt[6] | (stt[7] << 16);
+  reinterpret_cast<uint4 *>(tb.starts + blk * RADIX_BINS)[tid] = packed;
+  if (tid == 255) { tb.note[blk].entries = (int)run; tb.note[blk].above = sh_above; }
+  unsigned *gh = LAYER ? tb.hist1_tot + (size_t)b * RADIX_BINS : tb.hist1 + (size_t)seg * RADIX_BINS;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (cnt[i]) atomicAdd(&gh[tid * 8 + i], cnt[i]);
+    lh[tid * 8 + i] = stt[i];
   }
   __syncthreads();
-  if (LAST_HEAD_PASS) {
-    // this block's own counts: the emit kernel adds up those of the chunks in front of its own
-    const size_t blk = (size_t)blockIdx.x * h + c;
-    for (int i = tid; i < 1024; i += 256) chunk_hist[blk * 1024 + i] = (unsigned short)lh[i];
-    if (tid == 0) chunk_sure[blk] = sh_sure;
-  }
-  // layer scope: one plain store per block, the finishing kernel adds a head's blocks up
-  if (LAST_LAYER_PASS && tid == 0) chunk_sure[(size_t)blockIdx.x * h + c] = sh_sure;
-  unsigned *gh = hist.p[P] + (size_t)(b * h + c) * RADIX_BINS;
-  unsigned *gt = hist_tot + ((size_t)P * st.batch + b) * RADIX_BINS;
-  for (int i = tid; i < NB; i += 256) {
-    const unsigned v = lh[i];
-    if (v) {
-      // the layer scope looks at per-head counts only after its last pass
-      if (!LAYER || P == 2) atomicAdd(&gh[i], v);
-      if (LAYER) atomicAdd(&gt[i], v);
+  // (the order inside a bucket follows the atomics, but only the multiset of a bucket's last
+  // digits is ever used)
+  unsigned short *ent = tb.entries + blk * ENT_PER_BLOCK;
+#pragma unroll
+  for (int i = 0; i < EPB; ++i) {
+    const bool in = j0 + tid + 256 * i < j1;
+    if (in && (keys[i] >> 21) == d0) {
+      const unsigned slot = atomicAdd(&lh[(keys[i] >> 10) & 2047u], 1u);
+      if (slot < (unsigned)ENT_PER_BLOCK) ent[slot] = (unsigned short)(keys[i] & 1023u);
     }
   }
 }
 
-// Layer scope, after the third pass: Algorithm 1's counts f_c and the safeguard of Alg. 2 l.8.
-// One block of eight wavefronts per sequence.
-__global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, ChunkTab ct, int h, int w,
-                                                           int alpha_fix,
-                                                           HistSet hist,
-                                                           const unsigned *__restrict__ hist_tot,
-                                                           const int *__restrict__ chunk_sure,
-                                                           const uint2 *__restrict__ state,
-                                                           int *__restrict__ budgets,
-                                                           int *__restrict__ cu) {
+// Bucket d1 of one gather block: [first, first + count) in its entries.
+__device__ __forceinline__ void bucket_of(const TopkBufs &tb, size_t blk, unsigned d1, int &first,
+                                          int &count) {
+  const unsigned short *s = tb.starts + blk * RADIX_BINS;
+  const int total = min(max(tb.note[blk].entries, 0), ENT_PER_BLOCK);
+  const int a = min((int)s[d1], total);
+  const int e = d1 + 1 < (unsigned)RADIX_BINS ? min((int)s[d1 + 1], total) : total;
+  first = a;
+  count = max(e - a, 0);
+}
+
+// Inclusive scan of one int over the threads of a block of NT threads; returns the block total.
+template <int NT>
+__device__ __forceinline__ int block_scan_incl(int v, int &incl, int *sh /*[NT/64]*/) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  int x = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int u = __shfl_up(x, off);
+    if (lane >= off) x += u;
+  }
+  __syncthreads();
+  if (lane == 63) sh[wv] = x;
+  __syncthreads();
+  int before = 0, total = 0;
+  for (int i = 0; i < NT / 64; ++i) {
+    if (i < wv) before += sh[i];
+    total += sh[i];
+  }
+  incl = before + x;
+  return total;
+}
+
+// Last digit among the elements sharing the 22-bit prefix, from a finished 1024-bin histogram in
+// LDS: digit d2 whose bin holds rank r1, and the rank inside it = the number of ties to take.
+__device__ __forceinline__ void locate_last(const unsigned *lh2, int r1, unsigned &d2, int &ties,
+                                            unsigned *sh) {
+  Bins<1024> m;
+  const int t = threadIdx.x & 255;
+  const unsigned keep = threadIdx.x < 256 ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) m.v[i] = lh2[t * 4 + i] & keep;
+  locate<1024>(m, r1, d2, ties, sh);
+}
+
+// Layer scope, second kernel: Algorithm 1's counts f_c and the safeguard of Alg. 2 l.8.
+// One block of sixteen wavefronts per sequence.
+constexpr int FIN_NT = 1024;
+__global__ __launch_bounds__(FIN_NT) void alloc_finish_kernel(SeqTab st, ChunkTab ct, int h, int w,
+                                                              int alpha_fix, TopkBufs tb,
+                                                              int *__restrict__ budgets,
+                                                              int *__restrict__ cu) {
   __shared__ unsigned sh[8];
+  __shared__ int sh_scan[FIN_NT / 64];
+  __shared__ unsigned lh2[1024];
+  __shared__ unsigned held[HOLD_LAYER];                // (last digit << 6) | head
   __shared__ int sh_gt[64], sh_eq[64];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int b = blockIdx.x;
-  const int nsegs = st.batch * h;
+  const int Bp = st.Bp[b];
   if (tid < 64) { sh_gt[tid] = 0; sh_eq[tid] = 0; }
-  // Wavefront wv takes heads wv, wv+8, ...: the last pass's digit counts of the head (a lane
-  // loads its 16 bins at once) and the number of its elements above the threshold's 22-bit
-  // prefix, which the last histogram pass counted.  The first head's loads are issued before the
-  // threshold is known (they do not depend on it), so they share its round trip.
-  struct HeadBins { uint4 v2[4]; int sure; };
-  auto load_head = [&](int c) {
-    HeadBins hb;
-    const int cc = min(c, h - 1);
-    const uint4 *b2 = reinterpret_cast<const uint4 *>(hist.p[2] + (size_t)(b * h + cc) * RADIX_BINS) + lane * 4;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) hb.v2[i] = b2[i];
-    int sure = 0;                                      // the lanes stride over the head's blocks
-    for (int k = ct.off[b] + lane; k < ct.off[b + 1]; k += 64) sure += chunk_sure[(size_t)k * h + cc];
-    hb.sure = sure;
-    return hb;
-  };
-  HeadBins first = load_head(wv);
-  const Rank r = rank_before_pass<3, true>(st, h, b, 0, nullptr, hist, hist_tot, state, sh);
-  __syncthreads();
-  // r.prefix is the threshold key, r.krem how many threshold-valued elements are taken (in
-  // flat-index order, i.e. head by head).  Per head: elements strictly above the threshold are
-  // those above its 22-bit prefix plus those under the prefix with a larger last digit.
-  if (r.krem > 0) {
-    const unsigned d2 = digit_of<2>(r.prefix);
-    for (int c = wv; c < h; c += 8) {
-      const HeadBins hb = (c == wv) ? first : load_head(c);
-      int cnt = 0, eq = 0;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const unsigned a2[4] = {hb.v2[i].x, hb.v2[i].y, hb.v2[i].z, hb.v2[i].w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const unsigned bin = (unsigned)(lane * 16 + i * 4 + k);
-          if (bin > d2) cnt += (int)a2[k];
-          if (bin == d2) eq += (int)a2[k];
+  for (int i = tid; i < 1024; i += FIN_NT) lh2[i] = 0u;
+  const Bins<RADIX_BINS> m0 = load_bins<RADIX_BINS>(tb.hist_tot0 + (size_t)b * RADIX_BINS);
+  const Bins<RADIX_BINS> m1 = load_bins<RADIX_BINS>(tb.hist1_tot + (size_t)b * RADIX_BINS);
+  unsigned d0 = 0, d1 = 0, d2 = 0;
+  int r0 = 0, r1 = 0, ties = 0;
+  const int blk0 = ct.off[b] * h, blk1 = ct.off[b + 1] * h;      // this sequence's gather blocks
+  if (Bp > 0) {
+    locate<RADIX_BINS>(m0, Bp, d0, r0, sh);
+    locate<RADIX_BINS>(m1, r0, d1, r1, sh);
+    // the elements under (d0, d1): bucket d1 of every block.  Count them first.
+    // The block's elements above the prefix go to its head's count right away: those above d0,
+    // and under d0 those in the buckets after d1.
+    int mine_cnt = 0, longest = 0;
+    int first0 = 0, count0 = 0;                        // the first of this thread's blocks, kept
+    for (int k = blk0 + tid; k < blk1; k += FIN_NT) {
+      int first, count;
+      bucket_of(tb, (size_t)k, d1, first, count);
+      if (k == blk0 + tid) { first0 = first; count0 = count; }
+      mine_cnt += count;
+      longest = max(longest, count);
+      const int total = min(max(tb.note[k].entries, 0), ENT_PER_BLOCK);
+      const int over = tb.note[k].above + (total - first - count);
+      if (over) atomicAdd(&sh_gt[k % h], over);
+    }
+    int incl;
+    const int total = block_scan_incl<FIN_NT>(mine_cnt, incl, sh_scan);
+    // (a thread copies its blocks' buckets one element after the other: only short ones)
+    if (total <= HOLD_LAYER && !__syncthreads_or(longest > SERIAL_MAX)) {
+      // few: every thread copies its blocks' buckets into LDS, then digit and counts from there
+      int at = incl - mine_cnt;
+      for (int k = blk0 + tid; k < blk1; k += FIN_NT) {
+        int first = first0, count = count0;
+        if (k != blk0 + tid) bucket_of(tb, (size_t)k, d1, first, count);
+        const unsigned short *ent = tb.entries + (size_t)k * ENT_PER_BLOCK + first;
+        const unsigned head = (unsigned)(k % h);
+        for (int i = 0; i < count; ++i) {
+          const unsigned v = (((unsigned)ent[i] & 1023u) << 6) | head;
+          held[at++] = v;
+          atomicAdd(&lh2[v >> 6], 1u);
         }
       }
-      cnt += hb.sure;
+      __syncthreads();
+      locate_last(lh2, r1, d2, ties, sh);
+      for (int i = tid; i < total; i += FIN_NT) {
+        const unsigned v = held[i];
+        if ((v >> 6) > d2) atomicAdd(&sh_gt[v & 63u], 1);
+        if ((v >> 6) == d2) atomicAdd(&sh_eq[v & 63u], 1);
+      }
+    } else {
+      // a plateau: stream the buckets, a wavefront per block, once for the digit and once for
+      // the counts
+      for (int k = blk0 + wv; k < blk1; k += FIN_NT / 64) {
+        int first, count;
+        bucket_of(tb, (size_t)k, d1, first, count);
+        const unsigned short *ent = tb.entries + (size_t)k * ENT_PER_BLOCK + first;
+        for (int i = lane; i < count; i += 64) atomicAdd(&lh2[ent[i] & 1023u], 1u);
+      }
+      __syncthreads();
+      locate_last(lh2, r1, d2, ties, sh);
+      for (int k = blk0 + wv; k < blk1; k += FIN_NT / 64) {
+        int first, count;
+        bucket_of(tb, (size_t)k, d1, first, count);
+        const unsigned short *ent = tb.entries + (size_t)k * ENT_PER_BLOCK + first;
+        int gt = 0, eq = 0;
+        for (int i = lane; i < count; i += 64) {
+          const unsigned v = ent[i] & 1023u;
+          gt += v > d2;
+          eq += v == d2;
+        }
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) { cnt += __shfl_xor(cnt, off); eq += __shfl_xor(eq, off); }
-      if (lane == 0) { sh_gt[c] = cnt; sh_eq[c] = eq; }
+        for (int off = 32; off > 0; off >>= 1) { gt += __shfl_xor(gt, off); eq += __shfl_xor(eq, off); }
+        if (lane == 0) { atomicAdd(&sh_gt[k % h], gt); atomicAdd(&sh_eq[k % h], eq); }
+      }
     }
   }
   __syncthreads();
@@ -331,18 +426,17 @@ __global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, ChunkTab c
   __shared__ int sh_base[64];
   const int c = tid;
   const bool live = c < h;
-  const long long Bp = st.Bp[b];
   const long long one = 65536, a = alpha_fix;
   long long rem = -1;
   int base = 0;
   if (live) {
     long long before = 0;                              // threshold-valued elements of earlier heads
     for (int i = 0; i < c; ++i) before += sh_eq[i];
-    long long avail = (long long)r.krem - before;      // ties still to take when head c's turn comes
+    long long avail = (long long)ties - before;        // ties still to take when head c's turn comes
     if (avail < 0) avail = 0;
     const long long take = sh_eq[c] < avail ? sh_eq[c] : avail;
     const long long f = (long long)sh_gt[c] + take;     // Algorithm 1: B*_c = f_c
-    const long long num = (one - a) * h * f + a * Bp;   // x_c = num / den, den = 65536 h
+    const long long num = (one - a) * h * f + a * (long long)Bp;   // x_c = num / den, den = 65536 h
     // num / 65536 = (1-alpha) h f + alpha B' <= h f + B' < 2^32 (both sums are below 2^31), so
     // the division by den is a shift and one 32-bit division; the remainders recombine exactly
     const unsigned t = (unsigned)(num >> 16);
@@ -362,7 +456,7 @@ __global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, ChunkTab c
     given += sh_base[i];
     rank += (sh_rem[i] > rem) || (sh_rem[i] == rem && i < c);
   }
-  const int left = (int)(Bp - given);                  // 0 <= left < h
+  const int left = (int)((long long)Bp - given);       // 0 <= left < h
   if (rank < left) base += 1;                          // largest remainders, ties to the lower head
   budgets[b * h + c] = base;
   sh_base[c] = base;
@@ -375,51 +469,28 @@ __global__ __launch_bounds__(512) void alloc_finish_kernel(SeqTab st, ChunkTab c
   cu[b * h + c + 1] = run;
 }
 
-// Exclusive prefix sums of two per-thread counts over the 256 threads of a block.
-__device__ __forceinline__ void block_scan2(int a, int b, int &ea, int &eb, int *sh /*[8]*/) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  int ia = a, ib = b;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int ua = __shfl_up(ia, off), ub = __shfl_up(ib, off);
-    if (lane >= off) { ia += ua; ib += ub; }
-  }
-  __syncthreads();
-  if (lane == 63) { sh[wv] = ia; sh[4 + wv] = ib; }
-  __syncthreads();
-  int ba = 0, bb = 0;
-  for (int i = 0; i < wv; ++i) { ba += sh[i]; bb += sh[4 + i]; }
-  ea = ba + ia - a;
-  eb = bb + ib - b;
-}
+constexpr int EPT = SEL_CHUNK / 256;   // consecutive positions per thread in the emit kernel
 
-constexpr int EPT = SEL_CHUNK / 256;   // consecutive positions per thread in the emit kernels
-
-// Head scope, after the third pass: (threshold key, number of threshold-valued positions to take)
-__device__ __forceinline__ Rank head_threshold(const SeqTab &st, int h, int b, int c,
-                                               const HistSet &hist,
-                                               const uint2 *__restrict__ state, unsigned *sh) {
-  Rank r = rank_before_pass<3, false>(st, h, b, c, nullptr, hist, nullptr, state, sh);
-  if (r.krem <= 0) { r.prefix = 0xFFFFFFFFu; r.krem = 0; }   // no key is above, no tie is taken
-  return r;
-}
-
+// Head scope, second kernel.  Block (chunk, head) writes the kept positions of its 4096.
 __global__ __launch_bounds__(256) void emit_write_kernel(
-    SeqTab st, ChunkTab ct, int h, int w, const float *__restrict__ scores,
-    HistSet hist, const uint2 *__restrict__ state,
-    const unsigned short *__restrict__ chunk_hist, const int *__restrict__ chunk_sure,
+    SeqTab st, ChunkTab ct, int h, int w, const float *__restrict__ scores, TopkBufs tb,
     const int *__restrict__ budgets, const int *__restrict__ cu, int *__restrict__ indices,
     int rows_total) {
   __shared__ unsigned sh[8];
-  __shared__ int sh_base[2];
-  const int tid = threadIdx.x;
+  __shared__ int sh_scan[4];
+  __shared__ unsigned lh2[1024];
+  __shared__ unsigned held[HOLD_HEAD];                 // (last digit << 1) | (lies in an earlier block)
+  __shared__ int sh_cnt[2];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int b = find_seq(ct, st.batch, blockIdx.x);
-  int n = st.n[0], cfirst = ct.off[0], soff = st.score_off[0];   // as in the histogram kernel
+  int n = st.n[0], cfirst = ct.off[0], soff = st.score_off[0];   // as in the gather kernel
   if (b != 0) { n = st.n[b]; cfirst = ct.off[b]; soff = st.score_off[b]; }
   const int chunk = blockIdx.x - cfirst;
+  const int nchunks = (b != 0 ? ct.off[b + 1] : ct.off[1]) - cfirst;
   const int c = blockIdx.y;
   const int seg = b * h + c;
   const int out0 = cu[seg];
+  const int bud = budgets[seg];
   const float *row = scores + soff + (size_t)c * n;
 
   // this thread's 16 consecutive positions (loads issued before the scans below)
@@ -427,56 +498,90 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
   unsigned keys[EPT];
 #pragma unroll
   for (int i = 0; i < EPT; ++i) keys[i] = (j0 + i < n) ? key_of(row[j0 + i]) : 0u;
+  const Bins<RADIX_BINS> m0 = load_bins<RADIX_BINS>(tb.hist0 + (size_t)seg * RADIX_BINS);
+  const Bins<RADIX_BINS> m1 = load_bins<RADIX_BINS>(tb.hist1 + (size_t)seg * RADIX_BINS);
+  for (int i = tid; i < 1024; i += 256) lh2[i] = 0u;
+  if (tid < 2) sh_cnt[tid] = 0;
 
-  // What the earlier chunks of this head hold above / at the threshold, from what the last
-  // histogram pass left per block: elements above the threshold's 22-bit prefix, and the counts
-  // of the last digit under that prefix (this thread looks at digits 4*tid .. 4*tid+3).  The loads
-  // do not depend on the threshold, so they are issued in front of its scan, 32 chunks at a time.
-  constexpr int CB = 32;   // 32 chunks = 131072 positions of a head in one round trip
-  int pg = 0, pe = 0;
-  for (int k = tid; k < chunk; k += 256) pg += chunk_sure[(size_t)(cfirst + k) * h + c];
-  uint2 first[CB];
-#pragma unroll
-  for (int u = 0; u < CB; ++u) {
-    const int k = min(u, max(chunk - 1, 0));
-    first[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(cfirst + k) * h + c) * 1024 + tid * 4);
-  }
-  if (tid < 2) sh_base[tid] = 0;
-  const Rank r = head_threshold(st, h, b, c, hist, state, sh);
-  const unsigned thr = r.prefix;
-  const int ties = r.krem;
-  const unsigned d2 = thr & 1023u;
-  auto add_counts = [&](const uint2 &v) {
-    const unsigned cnt[4] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const unsigned bin = (unsigned)tid * 4u + i;
-      pg += bin > d2 ? (int)cnt[i] : 0;
-      pe += bin == d2 ? (int)cnt[i] : 0;
-    }
-  };
-  if (thr == 0xFFFFFFFFu) {
-    pg = 0;                                            // nothing is selected in this head: the
-  } else {                                             // histogram pass left no counts behind
-#pragma unroll
-    for (int u = 0; u < CB; ++u)
-      if (u < chunk) add_counts(first[u]);
-    for (int k0c = CB; k0c < chunk; k0c += CB) {
-      uint2 more[CB];
-#pragma unroll
-      for (int u = 0; u < CB; ++u) {
-        const int k = min(k0c + u, chunk - 1);
-        more[u] = *reinterpret_cast<const uint2 *>(chunk_hist + ((size_t)(cfirst + k) * h + c) * 1024 + tid * 4);
+  unsigned thr = 0xFFFFFFFFu;                          // no key is above, no tie is taken
+  int ties = 0;
+  int pg = 0, pe = 0;                                  // kept / threshold-valued positions of earlier blocks
+  if (bud > 0) {
+    unsigned d0, d1, d2;
+    int r0, r1;
+    locate<RADIX_BINS>(m0, bud, d0, r0, sh);
+    locate<RADIX_BINS>(m1, r0, d1, r1, sh);
+    // Every block of the head (thread k takes block k, k + 256, ...): how many of its elements
+    // share the prefix (d0, d1), and, for the blocks in front of this one, how many lie above it:
+    // those above d0, and under d0 those in the buckets after d1.
+    int mine_cnt = 0, longest = 0;
+    int first0 = 0, count0 = 0;                        // the first of this thread's blocks, kept
+    for (int k = tid; k < nchunks; k += 256) {
+      const size_t kb = (size_t)(cfirst + k) * h + c;
+      int first, count;
+      bucket_of(tb, kb, d1, first, count);
+      if (k == tid) { first0 = first; count0 = count; }
+      mine_cnt += count;
+      longest = max(longest, count);
+      if (k < chunk) {
+        const int total = min(max(tb.note[kb].entries, 0), ENT_PER_BLOCK);
+        pg += tb.note[kb].above + (total - first - count);
       }
-#pragma unroll
-      for (int u = 0; u < CB; ++u)
-        if (k0c + u < chunk) add_counts(more[u]);
     }
+    int incl;
+    const int total = block_scan_incl<256>(mine_cnt, incl, sh_scan);
+    if (total <= HOLD_HEAD && !__syncthreads_or(longest > SERIAL_MAX)) {
+      int at = incl - mine_cnt;
+      for (int k = tid; k < nchunks; k += 256) {
+        const size_t kb = (size_t)(cfirst + k) * h + c;
+        int first = first0, count = count0;
+        if (k != tid) bucket_of(tb, kb, d1, first, count);
+        const unsigned short *ent = tb.entries + kb * ENT_PER_BLOCK + first;
+        const unsigned earlier = k < chunk ? 1u : 0u;
+        for (int i = 0; i < count; ++i) {
+          const unsigned v = ent[i] & 1023u;
+          held[at++] = (v << 1) | earlier;
+          atomicAdd(&lh2[v], 1u);
+        }
+      }
+      __syncthreads();
+      locate_last(lh2, r1, d2, ties, sh);
+      for (int i = tid; i < total; i += 256) {
+        const unsigned v = held[i];
+        if (v & 1u) {
+          pg += (v >> 1) > d2;
+          pe += (v >> 1) == d2;
+        }
+      }
+    } else {
+      // a plateau: stream the buckets, a wavefront per block
+      for (int k = wv; k < nchunks; k += 4) {
+        const size_t kb = (size_t)(cfirst + k) * h + c;
+        int first, count;
+        bucket_of(tb, kb, d1, first, count);
+        const unsigned short *ent = tb.entries + kb * ENT_PER_BLOCK + first;
+        for (int i = lane; i < count; i += 64) atomicAdd(&lh2[ent[i] & 1023u], 1u);
+      }
+      __syncthreads();
+      locate_last(lh2, r1, d2, ties, sh);
+      for (int k = wv; k < chunk; k += 4) {
+        const size_t kb = (size_t)(cfirst + k) * h + c;
+        int first, count;
+        bucket_of(tb, kb, d1, first, count);
+        const unsigned short *ent = tb.entries + kb * ENT_PER_BLOCK + first;
+        for (int i = lane; i < count; i += 64) {
+          const unsigned v = ent[i] & 1023u;
+          pg += v > d2;
+          pe += v == d2;
+        }
+      }
+    }
+    thr = (d0 << 21) | (d1 << 10) | d2;
   }
   __syncthreads();
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) { pg += __shfl_xor(pg, off); pe += __shfl_xor(pe, off); }
-  if ((tid & 63) == 0) { atomicAdd(&sh_base[0], pg); atomicAdd(&sh_base[1], pe); }
+  if (lane == 0) { atomicAdd(&sh_cnt[0], pg); atomicAdd(&sh_cnt[1], pe); }
 
   int g = 0, e = 0;
 #pragma unroll
@@ -485,9 +590,10 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
     g += valid && keys[i] > thr;
     e += valid && keys[i] == thr;
   }
-  int eg, ee;
-  block_scan2(g, e, eg, ee, (int *)sh);                // its barriers also publish sh_base
-  int ng = sh_base[0] + eg, ne = sh_base[1] + ee;      // counts over all earlier positions of the head
+  // both counts in one scan (a block holds 4096 positions: 13 bits each)
+  int ige;
+  block_scan_incl<256>((g << 16) | e, ige, sh_scan);   // its barriers also publish sh_cnt
+  int ng = sh_cnt[0] + (ige >> 16) - g, ne = sh_cnt[1] + (ige & 0xFFFF) - e;   // over all earlier positions of the head
 #pragma unroll
   for (int i = 0; i < EPT; ++i) {
     const int j = j0 + i;
@@ -499,7 +605,6 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
     ne += ise;
   }
   if (chunk == 0) {
-    const int bud = budgets[seg];
     for (int rr = tid; rr < w; rr += 256)
       if ((unsigned)(out0 + bud + rr) < (unsigned)rows_total) indices[out0 + bud + rr] = n + rr;
   }
@@ -507,7 +612,7 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
 
 }  // namespace
 
-size_t plan_topk_bytes(const SeqTab &st, const Dims &dm) { return plan(st, dm).total; }
+size_t plan_topk_bytes(const SeqTab &st, const Dims &dm) { return plan(st, dm).bytes; }
 
 // Pipeline mode needs a scoring kernel that files the first digits itself: the MFMA path with the
 // max-pool fused into it.
@@ -520,8 +625,8 @@ TopkCarry plan_carry(const SeqTab &st, const Dims &dm, char *ws_topk) {
   TopkCarry tc;
   tc.zero_begin = (unsigned *)ws_topk;
   tc.zero_words = (unsigned)(p.zero_end / 4);
-  tc.hist0 = (unsigned *)(ws_topk + p.hist);
-  tc.hist_tot0 = (unsigned *)(ws_topk + p.hist_tot);
+  tc.hist0 = (unsigned *)(ws_topk + p.hist0);
+  tc.hist_tot0 = (unsigned *)(ws_topk + p.hist_tot0);
   return tc;
 }
 
@@ -536,49 +641,41 @@ void launch_topk_clear(const TopkCarry &tc, hipStream_t s) {
   launch_clear("score_hist_clear", tc.zero_begin, tc.zero_words, s);
 }
 
-static HistSet hist_set(char *ws, const TopkWs &p, const SeqTab &st, const Dims &dm, bool layer,
-                        bool carried) {
-  const size_t per_pass = (size_t)st.batch * dm.h_kv * RADIX_BINS;
-  unsigned *own = (unsigned *)(ws + (layer ? p.hist : p.hist_sel));
-  HistSet hs;
-  for (int q = 0; q < 3; ++q) hs.p[q] = own + q * per_pass;
-  if (!layer && carried) hs.p[0] = (unsigned *)(ws + p.hist);   // first digits: scope-independent
-  return hs;
+static TopkBufs bufs_of(char *ws, const TopkWs &p) {
+  TopkBufs tb;
+  tb.hist0 = (const unsigned *)(ws + p.hist0);
+  tb.hist_tot0 = (const unsigned *)(ws + p.hist_tot0);
+  tb.hist1 = (unsigned *)(ws + p.hist1);
+  tb.hist1_tot = (unsigned *)(ws + p.hist1_tot);
+  tb.starts = (unsigned short *)(ws + p.starts);
+  tb.note = (BlockNote *)(ws + p.note);
+  tb.entries = (unsigned short *)(ws + p.entries);
+  return tb;
 }
 
-template <bool LAYER>
-static void run_passes(const SeqTab &st, const Dims &dm, const float *scores,
-                       const int *budgets_in, const TopkWs &p, const ChunkTab &ct, char *ws,
-                       bool carried, hipStream_t s) {
-  const int h = dm.h_kv;
-  const HistSet hist = hist_set(ws, p, st, dm, LAYER, carried);
-  unsigned *hist_tot = (unsigned *)(ws + p.hist_tot);
-  uint2 *state = (uint2 *)(ws + p.state);
+// Outside pipeline mode a call is self-contained: it clears the histograms and counts the first
+// digits itself.
+static void first_digits(const char *init_name, const char *pass_name, const SeqTab &st,
+                         const ChunkTab &ct, int h, const float *scores, char *ws, const TopkWs &p,
+                         hipStream_t s) {
+  launch_clear(init_name, (unsigned *)ws, p.zero_end / 4, s);
   dim3 grid(ct.off[st.batch], h), block(256);
-#define ADAKV_PASS(P)                                                                          \
-  ADAKV_LAUNCH(LAYER ? "alloc_pass" #P : "select_pass" #P, (topk_hist_kernel<P, LAYER>), grid,   \
-               block, s, st, ct, h, scores, budgets_in, hist, hist_tot, state,                    \
-               (unsigned short *)(ws + p.chunk_hist), (int *)(ws + p.chunk_sure))
-  if (!carried) {
-    // this scope's own histograms (the layer scope's include the per-sequence totals)
-    if (LAYER) launch_clear("alloc_init", (unsigned *)(ws + p.hist), (p.hist_sel - p.hist) / 4, s);
-    else launch_clear("select_init", (unsigned *)(ws + p.hist_sel), (p.zero_end - p.hist_sel) / 4, s);
-    ADAKV_PASS(0);
-  }
-  ADAKV_PASS(1);
-  ADAKV_PASS(2);
-#undef ADAKV_PASS
+  ADAKV_LAUNCH(pass_name, topk_digit0_kernel, grid, block, s, st, ct, h, scores,
+               (unsigned *)(ws + p.hist0), (unsigned *)(ws + p.hist_tot0));
 }
 
 hipError_t launch_allocate(const SeqTab &st, const Dims &dm, const float *scores, int *budgets,
                            int *cu_seqlens, char *ws, bool carried, hipStream_t s) {
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
-  run_passes<true>(st, dm, scores, nullptr, p, ct, ws, carried, s);
-  ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(512), s, st, ct, dm.h_kv,
-               dm.w, dm.alpha_fix, hist_set(ws, p, st, dm, true, carried),
-               (const unsigned *)(ws + p.hist_tot), (const int *)(ws + p.chunk_sure),
-               (const uint2 *)(ws + p.state), budgets, cu_seqlens);
+  const int h = dm.h_kv;
+  if (!carried) first_digits("alloc_init", "alloc_pass0", st, ct, h, scores, ws, p, s);
+  const TopkBufs tb = bufs_of(ws, p);
+  dim3 grid(ct.off[st.batch], h), block(256);
+  ADAKV_LAUNCH("alloc_gather", (topk_gather_kernel<true>), grid, block, s, st, ct, h, scores,
+               (const int *)nullptr, tb);
+  ADAKV_LAUNCH("alloc_finish", alloc_finish_kernel, dim3(st.batch), dim3(FIN_NT), s, st, ct, h, dm.w,
+               dm.alpha_fix, tb, budgets, cu_seqlens);
   return hipGetLastError();
 }
 
@@ -587,12 +684,14 @@ hipError_t launch_select(const SeqTab &st, const Dims &dm, const float *scores,
                          bool carried, hipStream_t s) {
   const TopkWs p = plan(st, dm);
   const ChunkTab ct = make_chunks(st, SEL_CHUNK);
-  run_passes<false>(st, dm, scores, budgets, p, ct, ws, carried, s);
-  const HistSet hist = hist_set(ws, p, st, dm, false, carried);
-  dim3 grid(ct.off[st.batch], dm.h_kv), block(256);
-  ADAKV_LAUNCH("select_emit", emit_write_kernel, grid, block, s, st, ct, dm.h_kv, dm.w, scores,
-               hist, (const uint2 *)(ws + p.state), (const unsigned short *)(ws + p.chunk_hist),
-               (const int *)(ws + p.chunk_sure), budgets, cu_seqlens, indices, st.out_off[st.batch]);
+  const int h = dm.h_kv;
+  if (!carried) first_digits("select_init", "select_pass0", st, ct, h, scores, ws, p, s);
+  const TopkBufs tb = bufs_of(ws, p);
+  dim3 grid(ct.off[st.batch], h), block(256);
+  ADAKV_LAUNCH("select_gather", (topk_gather_kernel<false>), grid, block, s, st, ct, h, scores,
+               budgets, tb);
+  ADAKV_LAUNCH("select_emit", emit_write_kernel, grid, block, s, st, ct, h, dm.w, scores, tb, budgets,
+               cu_seqlens, indices, st.out_off[st.batch]);
   return hipGetLastError();
 }
 

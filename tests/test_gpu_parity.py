@@ -184,12 +184,14 @@ def _alloc_select(scores_np, w, B, alpha):
     return bud.cpu().numpy(), cu.cpu().numpy(), idx.cpu().numpy()
 
 
-@pytest.mark.parametrize("case", ["random", "quantised", "all_equal", "zeros_and_spikes", "plateaus"])
+@pytest.mark.parametrize("case", ["random", "quantised", "all_equal", "zeros_and_spikes", "plateaus",
+                                  "one_narrow_band", "long_bucket_in_one_block"])
 @pytest.mark.parametrize("alpha", [0.0, 0.2, 1.0])
 def test_allocate_select_bit_exact_on_oracle_scores(case, alpha):
     _say(f"allocate/select {case} alpha {alpha}")
     rng = np.random.default_rng(3)
     h, n, w = 4, 10007, 8
+    extra = ()
     if case == "random":
         s = rng.random((h, n)) ** np.array([1, 4, 16, 64])[:, None]
     elif case == "quantised":
@@ -198,10 +200,21 @@ def test_allocate_select_bit_exact_on_oracle_scores(case, alpha):
         s = np.full((h, n), 0.25)
     elif case == "zeros_and_spikes":
         s = np.zeros((h, n)); s[rng.integers(0, h, 300), rng.integers(0, n, 300)] = rng.random(300)
+    elif case == "one_narrow_band":
+        # every score inside one 22-bit key prefix (1024 consecutive floats), all last digits in use:
+        # far more prefix-sharing elements than a finishing block holds at once
+        base = np.array([0.3], np.float32).view(np.uint32)[0] & ~np.uint32(1023)
+        s = (base + rng.integers(0, 1024, (h, n)).astype(np.uint32)).view(np.float32)
+    elif case == "long_bucket_in_one_block":
+        # few prefix-sharing elements overall, but 1500 of them inside one block of 4096 positions
+        s = (rng.random((h, n)) ** 8).astype(np.float32)
+        base = np.array([0.3], np.float32).view(np.uint32)[0] & ~np.uint32(1023)
+        s[1, 100:1600] = (base + rng.integers(0, 1024, 1500).astype(np.uint32)).view(np.float32)
+        extra = (w * h + int((s > 0.31).sum()) + 700,)
     else:
         s = O.max_pool_same(rng.random((h, n)) ** 8, 7)
     s = s.astype(np.float32)
-    for B in (w * h, w * h + 1, w * h + 1000, w * h + h * n // 2, w * h + h * n - 1, w * h + h * n):
+    for B in (w * h, w * h + 1, w * h + 1000, w * h + h * n // 2, w * h + h * n - 1, w * h + h * n) + extra:
         bud, cu, idx = _alloc_select(s, w, B, alpha)
         rb, rcu = O.allocate(s, B, w, alpha)
         assert np.array_equal(bud, rb), (case, B, bud, rb)
@@ -419,7 +432,7 @@ def test_kernel_trace_names_every_kernel_and_costs_nothing_when_disarmed():
     torch.cuda.synchronize()
     names = [n for n, _ in tr.durations_us()]
     assert names[0].startswith("score_") and names[-1] == "compact"
-    assert sum(n.startswith("alloc_") for n in names) >= 3 and sum(n.startswith("select_") for n in names) >= 3
+    assert sum(n.startswith("alloc_") for n in names) >= 2 and sum(n.startswith("select_") for n in names) >= 2
     assert all(0 < us < 1e5 for _, us in tr.durations_us()) and tr.used == 2 * len(names)
     for key in ref:
         assert torch.equal(ref[key], out[key]), key
