@@ -29,13 +29,42 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X published peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# (workload, kernel) -> fetched + written bytes per launch, see profiles/llama8b_128k_hbm_traffic.md
-# and profiles/decode_llama8b_ragged_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {
-    ("llama8b_128k", "score_stats_mfma"): int((256.39 + 0.90) * 2 ** 20),
-    ("llama8b_128k", "score_weights_mfma"): int((257.04 + 4.10) * 2 ** 20),
-    ("llama8b_ragged/decode", "decode_attn"): int((44.86 + 1.03) * 2 ** 20),
-}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic(summary):
+    """HBM bytes per launch (fetched + written) of every kernel listed in a rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE summary under profiles/ (written from the counter CSVs, both counters
+    scaled by what they read for a 1 GiB copy): {name as bench.py traces it: bytes}, or {} when
+    the summary is not there.  Rows: | `kernel` | bench.py name | launches | FETCH KiB | fetched MiB
+    | WRITE KiB | written MiB | avg us |."""
+    path = os.path.join(PROFILES, summary)
+    out = {}
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 8 and cells[0].startswith("`"):
+            try:
+                out[cells[1]] = int((float(cells[4]) + float(cells[6])) * 2 ** 20)
+            except ValueError:
+                pass
+    return out
+
+
+def median_step_ms(torch, step, n_steps):
+    """Median over n_steps of the time of one step, from a pair of events around each on the
+    stream the step is issued on."""
+    pairs = []
+    for i in range(n_steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        step(i)
+        e1.record()
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in pairs)
+    return ts[len(ts) // 2]
 
 
 def algorithmic_bytes(wl, kept_rows):
@@ -142,8 +171,9 @@ def bench_decode(args):
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_attn", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name + "/decode", "decode_attn"))
+                "traffic": measured_traffic(f"decode_{wl.name}_hbm_traffic.md").get("decode_attn")
                 if args.budget_frac is None else None,
+                "traffic_source": f"profiles/decode_{wl.name}_hbm_traffic.md",
                 "algorithmic_bytes": int(dom_bytes), "avg_us": round(dom_us, 2)}
     cpu = None
     if not args.no_cpu_baseline:
@@ -293,10 +323,18 @@ def main():
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
     # counters read for a 1 GiB copy (profiles/llama8b_128k_hbm_traffic.md); only for the
     # workload and kernels that were profiled
-    traffic = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant))
+    plain = args.streams == 1 and not args.row_lse and args.pyramid is None and args.alpha is None
+    per_kernel_traffic = measured_traffic(f"{wl.name}_hbm_traffic.md") if plain else {}
+    traffic = per_kernel_traffic.get(dominant)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic, "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
+                "traffic": traffic, "traffic_source": f"profiles/{wl.name}_hbm_traffic.md" if traffic else None,
+                "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
+    # counter traffic of the whole step (every kernel of it, from the same summary) over the bytes
+    # the path has to move: what is above 1 is re-read or scratch traffic
+    step_traffic = (sum(per_kernel_traffic[k] for k in order) if per_kernel_traffic
+                    and all(k in per_kernel_traffic for k in order) else None)
+    median_ms = median_step_ms(torch, step, max(50, min(args.steps, 200))) if args.streams == 1 else None
 
     # ---- what a kernel that only reads reaches here: the same K buffers, rotated the same way ---
     sink = torch.empty(adakv.PROBE_SINK_BYTES, dtype=torch.uint8, device=dev)
@@ -371,8 +409,11 @@ def main():
                    "layer_budgets": "equal" if args.pyramid is None else
                    f"pyramid over {args.sets} layers, ratio {args.pyramid}: " + str([L.num_rows_out for L in layers]),
                    "layers_in_flight": max(1, args.streams)},
+        "median_ms_per_step": round(median_ms, 5) if median_ms is not None else None,
         "pipeline_hbm_frac": round(total_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "pipeline_algorithmic_bytes": total_alg,
+        "pipeline_traffic_bytes": step_traffic,
+        "pipeline_traffic_over_algorithmic": round(step_traffic / total_alg, 3) if step_traffic else None,
         "score_mfma_tflops": round(flops / (sum(v for k, v in kernels.items() if k.startswith("score_")) * 1e-6) / 1e12, 2),
         "kernels_us": {k: round(kernels[k], 2) for k in order},
         "stream_read": stream_read, "workload_stats": stats,

@@ -28,7 +28,11 @@
  *   - The caller owns every buffer.  The library allocates nothing, frees nothing and keeps
  *     no state between calls; scratch memory comes in through `ws` (size from
  *     adakv_workspace_bytes; its contents need not survive from one call to the next unless
- *     the caller asks for that with ADAKV_FLAG_PIPELINE).
+ *     the caller asks for that with ADAKV_FLAG_PIPELINE).  Two stated exceptions, neither on
+ *     the path of the method's calls: adakv_compress_static uses a built-in device array as its
+ *     scratch and remembers that array's address per GPU, and the measurement aid
+ *     adakv_trace_arm keeps the armed event list per calling host thread until
+ *     adakv_trace_disarm.
  *   - Every call only enqueues kernels on `hip_stream` (a hipStream_t, NULL = default stream)
  *     and returns; nothing synchronises with the host.  The number of output rows, sum_b B_b,
  *     is known before the call, so outputs are pre-sized by the caller.

@@ -459,10 +459,8 @@ DecodePlan plan_decode(const SeqTab &st, const Dims &dm, int headroom) {
   // Rows per workgroup.  Three workgroups fit on a compute unit, 768 on the chip: the split is
   // the multiple of 64 rows (one load round of a workgroup) that fills one such resident round,
   // so that all workgroups start together and none is left for a thin second round.
-#ifndef ADAKV_DECODE_ROUND_WGS
-#define ADAKV_DECODE_ROUND_WGS 752
-#endif
-  const long long room = ADAKV_DECODE_ROUND_WGS - nseg;      // the segments' last, partial splits
+  constexpr long long ROUND_WGS = 752;                       // a little under the 768 resident at once
+  const long long room = ROUND_WGS - nseg;                   // the segments' last, partial splits
   long long want = room > 64 ? (cap + room - 1) / room : cap / 512;
   if (want < 64) want = 64;
   const int split = (int)((want + 63) / 64 * 64);

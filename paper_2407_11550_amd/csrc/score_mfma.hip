@@ -42,13 +42,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TILE = 32;           // keys per MFMA tile
-#ifndef ADAKV_SWEEP1_INTERLEAVED
-#define ADAKV_SWEEP1_INTERLEAVED 1
-#endif
-#ifndef ADAKV_CHUNK_SWITCH_WGS
-#define ADAKV_CHUNK_SWITCH_WGS 512
-#endif
-constexpr long long CHUNK_SWITCH_WGS = ADAKV_CHUNK_SWITCH_WGS;   // fewer workgroups than this: halve the chunk
+constexpr long long CHUNK_SWITCH_WGS = 512;   // fewer workgroups than this: halve the chunk
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -126,7 +120,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // of the whole sequence.  At any moment the workgroups of a head then read neighbouring sets,
   // i.e. the chip streams one dense region of K instead of 64 regions 4 MiB apart (measured
   // with a plain-read kernel of the same shape: 6.2 against 5.5 TB/s).
-  constexpr bool INTER = PASS == 1 && ADAKV_SWEEP1_INTERLEAVED;
+  constexpr bool INTER = PASS == 1;
   const int nch = ct.off[b + 1] - ct.off[b];
   const int k0 = INTER ? 0 : (PASS == 2 && halo && kc0 > 0) ? kc0 - HALO : kc0;
   const int k1 = INTER ? n : (PASS == 2 && halo) ? min(n, kc1 + pool_r) : kc1;
@@ -140,9 +134,6 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // once per workgroup, addressed as a wave-uniform 64-bit base (scalar registers) plus a
   // 32-bit per-lane offset.  The loads of iterations it+1 .. it+DEPTH are in flight while
   // iteration it is computed (DEPTH register sets, two LDS buffers, one barrier per iteration).
-#ifndef ADAKV_FUSED_TILE
-#define ADAKV_FUSED_TILE 1
-#endif
   // register sets = iterations of loads in flight (a third set fits the statistics sweep's
   // registers and was measured: no faster; nor are four or six sets on the 512-row shape,
   // where a set is a single word per thread)
@@ -175,9 +166,6 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // channels.  Each workgroup therefore starts at a different point of its chunk and wraps
   // around (neither sweep depends on the order of the tiles).
   const int rot = (int)(((long long)chunk * iters) / nch);
-#ifndef ADAKV_SWEEP2_BACKWARDS
-#define ADAKV_SWEEP2_BACKWARDS 1
-#endif
   // Sweep 1 walks its chunk forwards from the rotated start; sweep 2 walks it backwards from
   // there, i.e. it begins with what sweep 1 read last.  Both sweeps have every chunk in flight
   // at once, so this, and not the order of the chunks, decides what the memory-side cache still
@@ -185,7 +173,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // reading it back hits most of it.
   auto phys = [&](int it) {
     if (INTER) return chunk + it * nch;                // a set of the whole sequence
-    if (PASS == 2 && ADAKV_SWEEP2_BACKWARDS) {
+    if (PASS == 2) {
       const int p = rot - 1 - it;
       return p < 0 ? p + iters : p;
     }
@@ -456,12 +444,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     if (have && prev_tile >= 0 && is_full(prev_tile)) {
       // the common case, straight-line: products of this tile, arithmetic of the previous one
       floatx16 accn[MB];
-      if (ADAKV_FUSED_TILE) {
-        fused_tile(kf, accn, accp, prev_tile);
-      } else {
-        mma(kf, accn);
-        epilogue(std::false_type{}, accp, prev_tile);
-      }
+      fused_tile(kf, accn, accp, prev_tile);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) accp[mb] = accn[mb];
       prev_tile = tile;
