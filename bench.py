@@ -224,6 +224,9 @@ def main():
     ap.add_argument("--row-lse", action="store_true",
                     help="compress path: hand adakv_score the prefill attention's row log-sum-exp, "
                          "which removes the statistics sweep (not the headline configuration)")
+    ap.add_argument("--pool-then-mean", action="store_true",
+                    help="compress path: ADAKV_FLAG_POOL_THEN_MEAN, the printed order of Alg. 2 l.4 (pool every "
+                         "window row, then average); not the headline configuration")
     ap.add_argument("--path", default="compress", choices=["compress", "decode"],
                     help="compress: the per-layer compression step (the headline); decode: append + "
                          "decode attention over the compressed cache")
@@ -253,7 +256,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload, alpha=args.alpha)
-    layer = adakv.Layer.from_workload(wl)
+    flags = adakv.binding.ADAKV_FLAG_POOL_THEN_MEAN if args.pool_then_mean else 0
+    layer = adakv.Layer.from_workload(wl, flags=flags)
     sets = [synth.generate(wl, layer=i, device=dev) for i in range(args.sets)]
     lses = [synth.prefill_row_lse(wl, q, K) if args.row_lse else None for q, K, _ in sets]
     # one layer description per input set: all alike, or the pyramidal variant's budgets per layer
@@ -265,7 +269,7 @@ def main():
         for l in range(args.sets):
             wll = synth.workload(args.workload, alpha=args.alpha)
             wll.B = [min(per_seq[b][l], wl.h_kv * wl.n[b]) + wh for b in range(wl.batch)]
-            layers.append(adakv.Layer.from_workload(wll))
+            layers.append(adakv.Layer.from_workload(wll, flags=flags))
         layer = max(layers, key=lambda L: L.num_rows_out)          # sizes the output buffers
     def make_bufs():
         return (torch.empty(adakv.workspace_bytes(layer), dtype=torch.uint8, device=dev),
@@ -323,7 +327,8 @@ def main():
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
     # counters read for a 1 GiB copy (profiles/llama8b_128k_hbm_traffic.md); only for the
     # workload and kernels that were profiled
-    plain = args.streams == 1 and not args.row_lse and args.pyramid is None and args.alpha is None
+    plain = (args.streams == 1 and not args.row_lse and args.pyramid is None and args.alpha is None
+             and not args.pool_then_mean)
     per_kernel_traffic = measured_traffic(f"{wl.name}_hbm_traffic.md") if plain else {}
     traffic = per_kernel_traffic.get(dominant)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
@@ -385,7 +390,8 @@ def main():
                 Kd = K[off[b]:off[b + 1]].double().cpu().numpy()
                 Vd = V[off[b]:off[b + 1]].float().cpu().numpy()
                 c0 = time.perf_counter()
-                O.compress_layer(qd, Kd, Vd, wl.n[b], wl.w, wl.pool_k, wl.B[b], wl.alpha)
+                O.compress_layer(qd, Kd, Vd, wl.n[b], wl.w, wl.pool_k, wl.B[b], wl.alpha,
+                                 order="pool_then_mean" if args.pool_then_mean else "mean_then_pool")
                 spent += time.perf_counter() - c0
                 done_tokens += wl.n[b]
             layers_done += 1
@@ -406,6 +412,8 @@ def main():
                    "w": wl.w, "pool_k": wl.pool_k, "B": wl.B, "alpha": wl.alpha, "batch": wl.batch,
                    "input_sets_rotated": len(sets),
                    "row_lse": "supplied by the caller (single sweep)" if args.row_lse else "computed (two sweeps)",
+                   "order": "pool every row, then mean (Alg. 2 l.4 as printed)" if args.pool_then_mean
+                   else "mean over the rows, then pool",
                    "layer_budgets": "equal" if args.pyramid is None else
                    f"pyramid over {args.sets} layers, ratio {args.pyramid}: " + str([L.num_rows_out for L in layers]),
                    "layers_in_flight": max(1, args.streams)},

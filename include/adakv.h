@@ -80,8 +80,9 @@ typedef enum {
 #define ADAKV_FLAG_POOL_THEN_MEAN 4u /* bit 2 of flags: adakv_score max-pools every window row along
                                        the keys first and averages the g*w rows afterwards (Alg. 2
                                        l.4 as printed) instead of averaging first (Section 3.4's
-                                       prose, the default).  Served by the plain-FMA kernels only
-                                       (far slower than the default path); pool_k/2 <= 100.     */
+                                       prose, the default).  On the matrix cores for pool_k/2 <= 7
+                                       (the pool is a sliding maximum across lanes, tiles overlap by
+                                       the radius), on the plain-FMA kernels up to pool_k/2 <= 100. */
 
 /*
  * One attention layer's compression problem, for `batch` independent sequences (Algorithm 1

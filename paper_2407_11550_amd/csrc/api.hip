@@ -65,14 +65,19 @@ static int build_tables(const adakv_layer *L, SeqTab &st, Dims &dm) {
 // Workspace: the scoring part first, the Top-k part behind it (they must not overlap: in
 // pipeline mode the scoring call already writes into the Top-k part).
 static bool pool_first(const adakv_layer *L) { return (L->flags & ADAKV_FLAG_POOL_THEN_MEAN) != 0; }
+// Which kernel family scores the layer: the matrix cores (16-bit inputs, at most 512 window rows
+// per KV head; with ADAKV_FLAG_POOL_THEN_MEAN a pool radius of at most 7), else the plain-FMA path.
+static bool on_mfma(const Dims &dm, const adakv_layer *L) {
+  return pool_first(L) ? mfma_pool_rows_supported(dm, L->dtype) : mfma_path_supported(dm, L->dtype);
+}
 static size_t topk_offset(const SeqTab &st, const Dims &dm, const adakv_layer *L) {
-  return align_up(plan_score(st, dm, L->dtype, pool_first(L)).total, 256);
+  return align_up(plan_score(st, dm, L->dtype, on_mfma(dm, L)).total, 256);
 }
 static size_t workspace_for(const SeqTab &st, const Dims &dm, const adakv_layer *L) {
   return topk_offset(st, dm, L) + plan_topk_bytes(st, dm) + 256;
 }
 static bool pipeline_mode(const adakv_layer *L, const Dims &dm) {
-  return (L->flags & ADAKV_FLAG_PIPELINE) != 0 && carry_supported(dm, L->dtype) && !pool_first(L);
+  return (L->flags & ADAKV_FLAG_PIPELINE) != 0 && carry_supported(dm, L->dtype) && on_mfma(dm, L);
 }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -197,13 +202,14 @@ int adakv_score(const adakv_layer *L, const void *q_window, const void *K, const
   if (!aligned16(q_window) || !aligned16(K) || !aligned16(scores)) return ADAKV_EUNSUPPORTED;
   if (!ws || ws_bytes < workspace_for(st, dm, L)) return ADAKV_EWORKSPACE;
   char *wsp = (char *)(((uintptr_t)ws + 255) & ~(uintptr_t)255);
-  ScorePlan pl = plan_score(st, dm, L->dtype, pool_first(L));
+  ScorePlan pl = plan_score(st, dm, L->dtype, on_mfma(dm, L));
   hipStream_t s = (hipStream_t)hip_stream;
   if (pool_first(L) && dm.pool_k / 2 > 100) return ADAKV_EUNSUPPORTED;
   TopkCarry tc = {nullptr, 0u, nullptr, nullptr};
   if (pipeline_mode(L, dm)) tc = plan_carry(st, dm, wsp + topk_offset(st, dm, L));
-  hipError_t e = (mfma_path_supported(dm, L->dtype) && !pool_first(L))
-                     ? launch_score_mfma(st, dm, L->dtype, q_window, K, row_lse, scores, wsp, pl, tc, s)
+  hipError_t e = on_mfma(dm, L)
+                     ? launch_score_mfma(st, dm, L->dtype, q_window, K, row_lse, scores, wsp, pl, tc,
+                                         pool_first(L), s)
                      : launch_score_generic(st, dm, L->dtype, q_window, K, row_lse, scores, wsp,
                                             pl, pool_first(L), s);
   return e == hipSuccess ? ADAKV_OK : ADAKV_EHIP;
@@ -387,13 +393,13 @@ int adakv_describe(const adakv_layer *L, int have_row_lse, char *out, size_t out
   const char *topk = pipeline_mode(L, dm) ? "carried" : "separate";
   const char *stats = have_row_lse ? "caller" : "sweep";
   int len;
-  if (mfma_path_supported(dm, L->dtype) && !pool_first(L)) {
+  if (on_mfma(dm, L)) {
     const MfmaVariant v = choose_mfma_variant(st, dm);
     len = snprintf(out, out_bytes,
-                   "score=mfma dtype=%s d=%d rows=%d mb=%d rs=%d kg=%d chunk=%d stats=%s lse=%s pool=%s topk=%s",
-                   dt, dm.d, dm.g * dm.w, v.mb, v.rs, v.kg, v.chunk, stats,
-                   have_row_lse ? "caller" : v.fuse_lse ? "fused" : "kernel",
-                   v.fuse_pool ? "fused" : "kernel", topk);
+                   "score=%s dtype=%s d=%d rows=%d mb=%d rs=%d kg=%d chunk=%d stats=%s lse=%s pool=%s topk=%s",
+                   pool_first(L) ? "mfma-pool-first" : "mfma", dt, dm.d, dm.g * dm.w, v.mb, v.rs, v.kg,
+                   v.chunk, stats, have_row_lse ? "caller" : v.fuse_lse ? "fused" : "kernel",
+                   pool_first(L) ? "rows" : v.fuse_pool ? "fused" : "kernel", topk);
   } else {
     len = snprintf(out, out_bytes, "score=%s dtype=%s d=%d rows=%d stats=%s lse=%s pool=kernel topk=%s",
                    pool_first(L) ? "fma-pool-first" : "fma", dt, dm.d, dm.g * dm.w, stats,

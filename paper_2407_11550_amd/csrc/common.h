@@ -73,7 +73,7 @@ struct ScorePlan {                  // byte offsets into the workspace
   size_t total;
   int part_chunk;                   // keys per partial-statistics chunk
 };
-ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype, bool pool_first);
+ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype, bool on_mfma);
 bool mfma_path_supported(const Dims &dm, int dtype);
 
 hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, const void *q,
@@ -81,7 +81,9 @@ hipError_t launch_score_generic(const SeqTab &st, const Dims &dm, int dtype, con
                                 const ScorePlan &pl, bool pool_first, hipStream_t s);
 hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, int dtype, const void *q,
                              const void *K, const float *row_lse, float *scores, char *ws,
-                             const ScorePlan &pl, const TopkCarry &tc, hipStream_t s);
+                             const ScorePlan &pl, const TopkCarry &tc, bool pool_rows,
+                             hipStream_t s);
+bool mfma_pool_rows_supported(const Dims &dm, int dtype);   // ADAKV_FLAG_POOL_THEN_MEAN on the matrix cores
 
 // ---- allocation and selection (select.hip) --------------------------------------------------
 // A score becomes a 32-bit key whose unsigned order is the float order (+0.0f turns -0 into +0;

@@ -267,11 +267,12 @@ __global__ __launch_bounds__(256) void pool_kernel(SeqTab st, ChunkTab ct, int p
   scores[base + j] = m;
 }
 
-ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype, bool pool_first) {
+ScorePlan plan_score(const SeqTab &st, const Dims &dm, int dtype, bool on_mfma) {
   ScorePlan p;
   // partial statistics: one (max, sum) pair per window row and chunk of keys; the plain-FMA
   // kernels cut a sequence into GEN_CHUNK keys, the matrix-core kernels into longer chunks
-  const bool mfma = mfma_path_supported(dm, dtype) && !pool_first;
+  const bool mfma = on_mfma;
+  (void)dtype;
   p.part_chunk = mfma ? choose_mfma_variant(st, dm).chunk : GEN_CHUNK;
   const size_t chunks = make_chunks(st, p.part_chunk).off[st.batch];
   const size_t RQ = (size_t)dm.h_q * dm.w;

@@ -45,8 +45,14 @@ constexpr int TILE = 32;           // keys per MFMA tile
 constexpr long long CHUNK_SWITCH_WGS = 512;   // fewer workgroups than this: halve the chunk
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr int MFMA_POOL_ROWS_MAX_RADIUS = 7;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// The value of the neighbouring lane: CTRL 0x130 = wave_shl:1 (lane i reads lane i+1), 0x138 =
+// wave_shr:1 (lane i reads lane i-1); the last / first lane of the wavefront reads 0.
+template <int CTRL> __device__ __forceinline__ unsigned wave_shift(unsigned x) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
 __device__ __forceinline__ bf16x8 as_bf16(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // One 32x32x16 product-accumulate on eight 16-bit elements per lane and operand; the fragments are
@@ -61,7 +67,12 @@ __device__ __forceinline__ floatx16 mfma16(bf16x8 a, bf16x8 b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int D, int MB, int RS, int KG, int CHUNK, int PASS, bool F16>
+// PR (sweep 2 only): the printed order of Alg. 2 l.4, max-pool along the keys in every window row
+// first, mean over the rows afterwards.  A lane of sweep 2 owns one key and 16 rows per row block,
+// so the pool is a sliding maximum across neighbouring lanes, with whole-wavefront shifts by one
+// lane.  Tiles then overlap by the pool radius on either side: only the inner 32 - 2r
+// lanes of a tile have all their neighbours and produce a score.
+template <int D, int MB, int RS, int KG, int CHUNK, int PASS, bool F16, bool PR = false>
 __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     SeqTab st, ChunkTab ct, Dims dm, float c_log2, const unsigned short *__restrict__ q,
     const unsigned short *__restrict__ K, const float *__restrict__ lse,
@@ -113,7 +124,8 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // front of the chunk (tiles stay aligned), the pool radius behind it.  No tile may start past
   // the last key somebody needs: the row clamp in load_set counts rows from the tile set's
   // first key and must never go below it.
-  const int pool_r = (PASS == 2 && halo) ? dm.pool_k / 2 : 0;
+  const int pool_r = (PASS == 2 && (halo || PR)) ? dm.pool_k / 2 : 0;
+  const int tstep = PR ? TILE - 2 * pool_r : TILE;     // keys a tile advances by
   // Sweep 1 does not need a workgroup's keys to be neighbours (its result is a (max, sum) pair
   // per row over whatever keys it saw), so there the tile sets of a head's workgroups are
   // interleaved: workgroup `chunk` of the sequence's nch takes sets chunk, chunk + nch, ...
@@ -124,7 +136,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   const int nch = ct.off[b + 1] - ct.off[b];
   const int k0 = INTER ? 0 : (PASS == 2 && halo && kc0 > 0) ? kc0 - HALO : kc0;
   const int k1 = INTER ? n : (PASS == 2 && halo) ? min(n, kc1 + pool_r) : kc1;
-  const int ntiles = (k1 - k0 + TILE - 1) / TILE;
+  const int ntiles = (k1 - k0 + tstep - 1) / tstep;
   const int row0 = rs * RW;                  // first window row of this wavefront
   const size_t head_row0 = (size_t)b * RQ + (size_t)c * R;
 
@@ -156,7 +168,8 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     ld_rel[i] = tl * TILE + row;
     wr_off[i] = tl * (TILE * STRIDE16) + row * STRIDE16 + tid % ROW16;
   }
-  const int rd_off = kg * (TILE * STRIDE16) + l32 * STRIDE16 + half;
+  // (with overlapping tiles the wavefront groups' tiles start tstep rows apart in the buffer)
+  const int rd_off = kg * (tstep * STRIDE16) + l32 * STRIDE16 + half;
   // interleaved: ceil(n / CHUNK) workgroups share ceil(n / (KG*TILE)) >= nch sets, at least one each
   const int sets_all = (ntiles + KG - 1) / KG;
   const int iters = INTER ? (sets_all - chunk + nch - 1) / nch : sets_all;
@@ -190,7 +203,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   const int need_lo = INTER ? 0 : max(kc0 - pool_r, 0);
   const int need_hi = INTER ? n - 1 : min(kc1 - 1 + pool_r, n - 1);
   auto load_set = [&](u32x4 (&g)[LDPT], int it) {
-    const int key0 = k0 + it * KG * TILE;              // first key of the iteration
+    const int key0 = k0 + it * KG * tstep - (PR ? pool_r : 0);   // first key of the iteration
     // both bounds are kept at or above zero, so the clamped row is never negative (it goes
     // through an unsigned 24-bit multiply); key0 <= need_hi holds by the choice of k1 above
     const int lim = max(need_hi - key0, 0), lo = max(need_lo - key0, 0);
@@ -350,6 +363,39 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
         rl[mb] = rl[mb] * fast_exp2(rm[mb] - ref) + sum;
         rm[mb] = nm;
       }
+    } else if (PR) {
+      // acc[mb][r]: window row row0 + mb*32 + 8*(r/4) + 4*half + r%4, key k0 + tile*tstep - pool_r + l32.
+      // The weights themselves are pooled: they are non-negative floats, whose order is the order
+      // of their bit patterns, so one integer max with the neighbouring lane as its operand does a
+      // step of the sliding maximum.  Keys outside the sequence count as weight 0, which never
+      // wins (the pool window is clipped to the sequence).
+      const int j = tile * tstep - pool_r + l32;       // key, counted from k0
+      const unsigned inseq = (k0 + j >= 0 && k0 + j < n) ? 0xFFFFFFFFu : 0u;
+      unsigned p[MB][16];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          p[mb][r] = __float_as_uint(fast_exp2(fmaf(acc[mb][r], c_log2, -l2[mb][r]))) & inseq;
+      for (int t = 0; t < pool_r; ++t) {               // keys j .. j + pool_r
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) p[mb][r] = max(p[mb][r], wave_shift<0x130>(p[mb][r]));
+      }
+      for (int t = 0; t < pool_r; ++t) {               // keys j - pool_r .. j + pool_r
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) p[mb][r] = max(p[mb][r], wave_shift<0x138>(p[mb][r]));
+      }
+      float sum = 0.0f;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += __uint_as_float(p[mb][r]);
+      sum += __shfl_xor(sum, 32);
+      if (half == 0 && l32 >= pool_r && l32 < TILE - pool_r && j < k1 - k0) sh_part[rs][j] = sum;
     } else {
       // acc[mb][r]: window row row0 + mb*32 + 8*(r/4) + 4*half + r%4, key base + l32
       float sum = 0.0f;
@@ -441,7 +487,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     load_set(ga, phys(min(it + DEPTH, iters - 1)));
     const int tile = phys(it) * KG + kg;
     const bool have = tile < ntiles;
-    if (have && prev_tile >= 0 && is_full(prev_tile)) {
+    if (!PR && have && prev_tile >= 0 && is_full(prev_tile)) {
       // the common case, straight-line: products of this tile, arithmetic of the previous one
       floatx16 accn[MB];
       fused_tile(kf, accn, accp, prev_tile);
@@ -560,7 +606,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
 template <bool F16, int D, int MB, int RS, int KG, int CHUNK>
 void run_mfma(const MfmaVariant &v, const SeqTab &st, const Dims &dm, const void *q, const void *K,
               const float *row_lse, float *scores, char *ws, const ScorePlan &pl,
-              const TopkCarry &tc, hipStream_t s) {
+              const TopkCarry &tc, bool pool_rows, hipStream_t s) {
   const ChunkTab ct = make_chunks(st, CHUNK);
   const int nblk = ct.off[st.batch] * dm.h_kv;
   const float c_log2 = dm.scale * LOG2E;
@@ -581,6 +627,13 @@ void run_mfma(const MfmaVariant &v, const SeqTab &st, const Dims &dm, const void
   } else if (tc.zero_begin) {
     launch_topk_clear(tc, s);                 // no statistics sweep to do the clearing
   }
+  if (pool_rows) {
+    // the printed order of Alg. 2 l.4: the sweep pools every row itself and writes final scores
+    ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 2, F16, true>),
+                 dim3(nblk), block, s, st, ct, dm, c_log2, (const unsigned short *)q,
+                 (const unsigned short *)K, use_lse, part, scores, 0, tc);
+    return;
+  }
   ADAKV_LAUNCH("score_weights_mfma", (score_mfma_kernel<D, MB, RS, KG, CHUNK, 2, F16>), dim3(nblk),
                block, s, st, ct, dm, c_log2, (const unsigned short *)q, (const unsigned short *)K,
                use_lse, part, fuse_pool ? scores : raw, fuse_pool ? 1 : 0, tc);
@@ -590,10 +643,10 @@ void run_mfma(const MfmaVariant &v, const SeqTab &st, const Dims &dm, const void
 template <int D, bool F16>
 hipError_t run_mfma_d(const MfmaVariant &v, const SeqTab &st, const Dims &dm, const void *q,
                       const void *K, const float *row_lse, float *scores, char *ws,
-                      const ScorePlan &pl, const TopkCarry &tc, hipStream_t s) {
+                      const ScorePlan &pl, const TopkCarry &tc, bool pool_rows, hipStream_t s) {
 #define ADAKV_MFMA_CASE(MB, RS, KG, CHUNK)                                                      \
   if (v.mb == MB && v.rs == RS && v.kg == KG && v.chunk == CHUNK) {                             \
-    run_mfma<F16, D, MB, RS, KG, CHUNK>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s);       \
+    run_mfma<F16, D, MB, RS, KG, CHUNK>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s); \
     return hipGetLastError();                                                                   \
   }
   ADAKV_MFMA_CASE(1, 1, 4, 2048)
@@ -651,13 +704,20 @@ MfmaVariant choose_mfma_variant(const SeqTab &st, const Dims &dm) {
 
 hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, int dtype, const void *q,
                              const void *K, const float *row_lse, float *scores, char *ws,
-                             const ScorePlan &pl, const TopkCarry &tc, hipStream_t s) {
+                             const ScorePlan &pl, const TopkCarry &tc, bool pool_rows,
+                             hipStream_t s) {
   const MfmaVariant v = choose_mfma_variant(st, dm);
   if (dtype == ADAKV_FP16)
-    return dm.d == 64 ? run_mfma_d<64, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s)
-                      : run_mfma_d<128, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s);
-  return dm.d == 64 ? run_mfma_d<64, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s)
-                    : run_mfma_d<128, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, s);
+    return dm.d == 64 ? run_mfma_d<64, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s)
+                      : run_mfma_d<128, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s);
+  return dm.d == 64 ? run_mfma_d<64, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s)
+                    : run_mfma_d<128, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s);
+}
+
+// The printed order of Alg. 2 l.4 (pool every row, then average) runs on the matrix cores as long
+// as a tile keeps at least 18 of its 32 lanes (pool radius up to 7); wider pools take the FMA path.
+bool mfma_pool_rows_supported(const Dims &dm, int dtype) {
+  return mfma_path_supported(dm, dtype) && dm.pool_k / 2 <= MFMA_POOL_ROWS_MAX_RADIUS;
 }
 
 }  // namespace adakv

@@ -558,11 +558,20 @@ POOL_FIRST_CASES = [
     (2, 1, 128, 3, 201, [333], torch.float32, False),      # the largest pool radius this order takes
     (8, 2, 128, 8, 7, [900], torch.float16, False),
     (4, 2, 64, 16, 3, [1300, 70], torch.float16, False),
+    # pool radius beyond what the matrix-core kernels take in this order (7): the plain-FMA kernels
+    (8, 2, 128, 8, 17, [1100], torch.bfloat16, False),
+    (8, 2, 64, 8, 21, [900, 300], torch.bfloat16, False),
+    (8, 2, 128, 8, 19, [700], torch.float16, True),
+    (4, 2, 64, 16, 17, [1300], torch.float16, False),
 ]
+# ... and every instantiation of the matrix-core kernels in this order: the shapes of
+# variant_shapes() that are scored on the matrix cores, with their own pool kernels (3 to 9)
+POOL_FIRST_CASES += [(h_q, h, d, w, k, [n], dt, False) for h_q, h, d, w, k, n, _, dt in variant_shapes()
+                     if h_q // h * w <= 512 and k // 2 <= 7]
 
 
 @pytest.mark.parametrize("case", POOL_FIRST_CASES,
-                         ids=["bf16", "fp32", "row_lse", "no_pool", "radius100", "fp16", "fp16_d64"])
+                         ids=lambda c: "hq%d_h%d_d%d_w%d_k%d_n%d_%s%s" % (c[:5] + (c[5][0], str(c[6])[6:], "_lse" if c[7] else "")))
 def test_pool_then_mean_flag_matches_oracle_order(case):
     """ADAKV_FLAG_POOL_THEN_MEAN: scores follow the oracle's order="pool_then_mean"; the later
     steps are exact functions of the scores as always."""
@@ -592,6 +601,25 @@ def test_pool_then_mean_flag_matches_oracle_order(case):
         assert not torch.equal(plain, out["scores"])                      # the head's peak hides the order)
     elif k == 1:
         assert_scores_close(plain.cpu().numpy(), out["scores"].cpu().numpy(), "orders agree without pooling")
+
+
+def test_pool_then_mean_flag_at_full_size():
+    """The printed order of Alg. 2 l.4 on a complete llama8b_32k layer (matrix-core kernels,
+    pipeline mode): every score against the oracle's order="pool_then_mean", the rest exact."""
+    from paper_2407_11550_amd.binding import ADAKV_FLAG_POOL_THEN_MEAN
+    _say("pool then mean, llama8b_32k")
+    wl = synth.workload("llama8b_32k")
+    q, K, V = synth.generate(wl, device=DEV)
+    layer = adakv.Layer.from_workload(wl, flags=ADAKV_FLAG_POOL_THEN_MEAN)
+    assert adakv.describe(layer)["score"] == "mfma-pool-first"
+    out = adakv.compress(layer, q, K, V)
+    torch.cuda.synchronize()
+    ref = O.score(to_f64(q[0]), to_f64(K), wl.n[0], wl.w, wl.pool_k, order="pool_then_mean")
+    sc = out["scores"].cpu().numpy()
+    assert_scores_close(sc, ref, "pool then mean, llama8b_32k")
+    assert_exact_on_scores(out, sc, wl, K, V)
+    plain = adakv.score(adakv.Layer.from_workload(wl), q, K)
+    assert not torch.equal(plain, out["scores"])
 
 
 @pytest.mark.parametrize("dt", [torch.bfloat16, torch.float32, torch.float16], ids=["bf16", "fp32", "fp16"])

@@ -21,13 +21,15 @@ def _variants_reached():
     layers += [synth.workload(nm) for nm in ("tiny", "llama8b_32k", "llama8b_128k", "llama8b_ragged", "llama70b_128k")]
     described = [adakv.describe(adakv.Layer.from_workload(wl)) for wl in layers]
     for h_q, h, d, w, k, n, dt, _ in G.POOL_FIRST_CASES:
-        wl = synth.small_workload(h_q, h, d, w, k, n, [h * (w + 1)] * len(n), dtype=dt)
+        wl = synth.small_workload(h_q, h, d, w, k, n, [h * (w + max(1, nb // 10)) for nb in n], dtype=dt)
         described.append(adakv.describe(adakv.Layer.from_workload(wl, flags=adakv.binding.ADAKV_FLAG_POOL_THEN_MEAN)))
     for v in described:
         if v["score"] == "mfma":
             seen.add((v["dtype"], int(v["d"]), int(v["mb"]), int(v["rs"]), int(v["kg"]), int(v["chunk"])))
             seen.add(("lse", v["lse"], int(v["d"])))
             seen.add(("pool", v["pool"], int(v["d"])))
+        elif v["score"] == "mfma-pool-first":
+            seen.add(("pool-first", v["dtype"], int(v["d"]), int(v["mb"]), int(v["rs"]), int(v["kg"]), int(v["chunk"])))
         else:
             seen.add((v["score"], v["dtype"], int(v["d"])))
     return seen
@@ -41,6 +43,8 @@ def test_gpu_shapes_reach_every_scoring_variant(lib):
                                   (2, 2, 2, 2048), (2, 4, 1, 1024)):
             want.add((dt, d, mb, rs, kg, chunk))
         want.add((dt, d, 2, 8, 1, 1024) if d == 128 else (dt, d, 4, 4, 1, 1024))
+    # the same instantiations once more for the other order of pooling and averaging
+    want |= {("pool-first",) + v for v in set(want)}
     for d in (64, 128):
         want |= {("lse", "fused", d), ("lse", "kernel", d), ("pool", "fused", d), ("pool", "kernel", d)}
     for dt, d in itertools.product(("bf16", "fp16", "fp32"), (64, 128)):
@@ -58,7 +62,9 @@ def test_describe_follows_flags_and_rejects_what_score_rejects(lib):
     assert adakv.describe(adakv.Layer.from_workload(wl, flags=adakv.binding.ADAKV_FLAG_PIPELINE))["topk"] == "carried"
     assert adakv.describe(adakv.Layer.from_workload(wl), row_lse=True)["stats"] == "caller"
     first = adakv.describe(adakv.Layer.from_workload(wl, flags=adakv.binding.ADAKV_FLAG_POOL_THEN_MEAN))
-    assert first["score"] == "fma-pool-first"
+    assert first["score"] == "mfma-pool-first" and first["pool"] == "rows"
+    wl.pool_k = 17                                       # radius 8: beyond what that kernel pools across lanes
+    assert adakv.describe(adakv.Layer.from_workload(wl, flags=adakv.binding.ADAKV_FLAG_POOL_THEN_MEAN))["score"] == "fma-pool-first"
     wl.pool_k = 4
     try:
         adakv.describe(adakv.Layer.from_workload(wl))
