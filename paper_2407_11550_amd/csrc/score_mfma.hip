@@ -323,6 +323,8 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   float rm[MB], rl[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) { rm[mb] = -INFINITY; rl[mb] = 0.0f; }
+  bool have_ref = false;                       // (the same for all lanes) a first tile has set rm
+  constexpr bool LAZY_REF = RPAD > 128;
 
 
   // The matrix products of a tile and the softmax arithmetic on the PREVIOUS tile's products are
@@ -419,7 +421,39 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     floatx16 a[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) a[mb] = floatx16{0};
-    if (PASS == 1) {
+    if (PASS == 1 && LAZY_REF && have_ref) {
+      // (shapes with more than 128 window rows per KV head, which are bound by their arithmetic;
+      // on the 128-row shapes the sweep is bound by memory and the shorter code measured 2 us slower)
+      // Once a row has a reference, its tiles' exponentials are taken against that same reference
+      // without looking for the tile's maximum first: a sum of exp2(x - ref) is as accurate for one
+      // reference as for another as long as nothing overflows (x - ref < 128), and what underflows
+      // (x - ref < -126) is negligible beside the term that set the reference, which is 1.  An
+      // overflow shows as a sum that is not finite; the tile is then folded in again the careful way.
+      float sum[MB];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) sum[mb] = 0.0f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const int slot = s * MB + mb;
+#pragma unroll
+          for (int v = slot * VALS / SLOTS; v < (slot + 1) * VALS / SLOTS; ++v)
+            sum[v / 16] += fast_exp2(fmaf(acc[v / 16][v % 16], c_log2, -rm[v / 16]));
+          a[mb] = mfma16<F16>(kf[s], qf[mb][s], a[mb]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      bool bad = false;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) bad |= !(sum[mb] < INFINITY);
+      if (__any(bad)) {
+        epilogue(std::false_type{}, acc, tile);
+      } else {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) rl[mb] += sum[mb];
+      }
+    } else if (PASS == 1) {
       // slots 0 .. MB-1 find the row blocks' tile maxima, the others share the exponentials
       constexpr int ESLOTS = SLOTS - MB;
       float ref[MB], nmx[MB], sum[MB];
@@ -450,6 +484,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
         rl[mb] = rl[mb] * fast_exp2(rm[mb] - ref[mb]) + sum[mb];
         rm[mb] = nmx[mb];
       }
+      have_ref = true;
     } else {
       float sum = 0.0f;
 #pragma unroll
