@@ -122,6 +122,25 @@ def test_every_scoring_variant_matches_oracle(shape):
     _check_all(wl, q, K, V, out)
 
 
+def test_statistics_sweep_survives_logits_far_above_its_first_tile():
+    """The statistics sweep of the many-row shapes keeps the reference its first tile gave a row
+    and only looks for a new maximum when a sum overflows.  Here the first 64 keys are tiny and
+    later keys give logits more than 128 powers of two above them, so that path is taken."""
+    _say("statistics sweep: overflow of the kept reference")
+    wl = synth.small_workload(8, 2, 128, 64, 7, 3000, 2 * 300, dtype=torch.bfloat16, seed=77)   # 256 rows per head
+    q, K, V = synth.generate(wl, device=DEV)
+    q = (q.float() * 4).to(torch.bfloat16)
+    K = K.float()
+    K[:64] *= 0.01
+    K[64:] *= 6
+    K = K.to(torch.bfloat16)
+    logits = torch.einsum("hwd,nd->hwn", q[0, :4].float(), K[:3000, 0].float()) / 128 ** 0.5
+    assert float((logits[:, :, 64:].amax(-1) - logits[:, :, :64].amax(-1)).max()) * 1.4427 > 128
+    _, out = _run(wl, q, K, V)
+    assert adakv.describe(adakv.Layer.from_workload(wl))["rs"] == "4"
+    _check_all(wl, q, K, V, out)
+
+
 def test_tiny_config():
     _say("tiny config")
     wl = synth.workload("tiny")
