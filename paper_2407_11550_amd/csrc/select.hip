@@ -315,6 +315,98 @@ __device__ __forceinline__ int block_scan_incl(int v, int &incl, int *sh /*[NT/6
   return total;
 }
 
+// Last digits of a streamed bucket go to a visitor with two members: same(v, ok, times) when all
+// of a lane's `times` entries carry the digit v, in every lane with ok set (a plateau of one
+// value), and one(v, ok) for a single entry otherwise.  Both are called by a whole wavefront.
+//
+// The visitor that files them in a 1024-bin histogram in LDS.  64 atomics on one LDS word run one
+// after the other, so while the lanes agree, call after call, the wavefront only keeps a running
+// (digit, count) pair and adds it when the digit changes (and in flush() at the end).
+struct WaveHist {
+  unsigned *lh;
+  unsigned run_digit, run_count;                       // the same in all lanes
+  __device__ __forceinline__ explicit WaveHist(unsigned *bins) : lh(bins), run_digit(0u), run_count(0u) {}
+  __device__ __forceinline__ void flush() {
+    if (run_count && (threadIdx.x & 63) == 0) atomicAdd(&lh[run_digit], run_count);
+    run_count = 0u;
+  }
+  __device__ __forceinline__ void same(unsigned digit, bool ok, unsigned times) {
+    const unsigned long long act = __ballot(ok);
+    if (act == 0) return;
+    const int leader = __ffsll((long long)act) - 1;
+    const unsigned dl = (unsigned)__builtin_amdgcn_readlane((int)digit, leader);
+    if (__ballot(ok && digit != dl) == 0) {
+      if (dl != run_digit) flush();
+      run_digit = dl;
+      run_count += (unsigned)__popcll(act) * times;
+    } else if (ok) {
+      atomicAdd(&lh[digit], times);
+    }
+  }
+  __device__ __forceinline__ void one(unsigned digit, bool ok) {
+    if (ok) atomicAdd(&lh[digit], 1u);
+  }
+};
+
+// The visitor that counts the entries above and at the last digit d2.
+struct CountAbove {
+  unsigned d2;
+  int gt, eq;
+  __device__ __forceinline__ explicit CountAbove(unsigned digit) : d2(digit), gt(0), eq(0) {}
+  __device__ __forceinline__ void same(unsigned v, bool ok, unsigned times) {
+    gt += (ok && v > d2) ? (int)times : 0;
+    eq += (ok && v == d2) ? (int)times : 0;
+  }
+  __device__ __forceinline__ void one(unsigned v, bool ok) {
+    gt += ok && v > d2;
+    eq += ok && v == d2;
+  }
+};
+
+// Every entry of a bucket goes to the visitor f, called by a whole wavefront the same number of
+// times in every lane.  Long buckets only occur on plateaus, where a block's elements under d0 all
+// share one bucket that starts at entry 0: 16-byte loads (eight entries) when the bucket starts at
+// a multiple of eight entries, eight of them in flight per lane (a whole block's 4096 entries in
+// one round trip); two-byte loads, eight in flight, otherwise and for the tail.
+template <class F>
+__device__ __forceinline__ void for_bucket(const unsigned short *ent, int first, int count, F &f) {
+  const int lane = threadIdx.x & 63;
+  const unsigned short *p = ent + first;
+  int done = 0;
+  if ((first & 7) == 0) {
+    const uint4 *q = reinterpret_cast<const uint4 *>(p);
+    const int vecs = count / 8;                        // whole 16-byte words
+    for (int v0 = 0; v0 < vecs; v0 += 512) {
+      uint4 w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) w[u] = q[min(v0 + u * 64 + lane, vecs - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool ok = v0 + u * 64 + lane < vecs;
+        const unsigned x[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+        const bool all8 = x[0] == x[1] && x[1] == x[2] && x[2] == x[3] && (x[0] >> 16) == (x[0] & 0xFFFFu);
+        if (__ballot(ok && !all8) == 0) {
+          f.same(x[0] & 1023u, ok, 8u);
+        } else {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            f.one(x[k] & 1023u, ok);
+            f.one((x[k] >> 16) & 1023u, ok);
+          }
+        }
+      }
+    }
+    done = vecs * 8;
+  }
+  for (int i0 = done; i0 < count; i0 += 512) {
+    unsigned v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[min(i0 + u * 64 + lane, count - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) f.one(v[u] & 1023u, i0 + u * 64 + lane < count);
+  }
+}
+
 // Last digit among the elements sharing the 22-bit prefix, from a finished 1024-bin histogram in
 // LDS: digit d2 whose bin holds rank r1, and the rank inside it = the number of ties to take.
 __device__ __forceinline__ void locate_last(const unsigned *lh2, int r1, unsigned &d2, int &ties,
@@ -394,24 +486,25 @@ __global__ __launch_bounds__(FIN_NT) void alloc_finish_kernel(SeqTab st, ChunkTa
     } else {
       // a plateau: stream the buckets, a wavefront per block, once for the digit and once for
       // the counts
+      // (the next block's bucket is looked up while the current one streams)
+      WaveHist wh(lh2);
+      int nfirst = 0, ncount = 0;
+      if (blk0 + wv < blk1) bucket_of(tb, (size_t)(blk0 + wv), d1, nfirst, ncount);
       for (int k = blk0 + wv; k < blk1; k += FIN_NT / 64) {
-        int first, count;
-        bucket_of(tb, (size_t)k, d1, first, count);
-        const unsigned short *ent = tb.entries + (size_t)k * ENT_PER_BLOCK + first;
-        for (int i = lane; i < count; i += 64) atomicAdd(&lh2[ent[i] & 1023u], 1u);
+        const int first = nfirst, count = ncount;
+        if (k + FIN_NT / 64 < blk1) bucket_of(tb, (size_t)(k + FIN_NT / 64), d1, nfirst, ncount);
+        for_bucket(tb.entries + (size_t)k * ENT_PER_BLOCK, first, count, wh);
       }
+      wh.flush();
       __syncthreads();
       locate_last(lh2, r1, d2, ties, sh);
+      if (blk0 + wv < blk1) bucket_of(tb, (size_t)(blk0 + wv), d1, nfirst, ncount);
       for (int k = blk0 + wv; k < blk1; k += FIN_NT / 64) {
-        int first, count;
-        bucket_of(tb, (size_t)k, d1, first, count);
-        const unsigned short *ent = tb.entries + (size_t)k * ENT_PER_BLOCK + first;
-        int gt = 0, eq = 0;
-        for (int i = lane; i < count; i += 64) {
-          const unsigned v = ent[i] & 1023u;
-          gt += v > d2;
-          eq += v == d2;
-        }
+        const int first = nfirst, count = ncount;
+        if (k + FIN_NT / 64 < blk1) bucket_of(tb, (size_t)(k + FIN_NT / 64), d1, nfirst, ncount);
+        CountAbove ca(d2);
+        for_bucket(tb.entries + (size_t)k * ENT_PER_BLOCK, first, count, ca);
+        int gt = ca.gt, eq = ca.eq;
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) { gt += __shfl_xor(gt, off); eq += __shfl_xor(eq, off); }
         if (lane == 0) { atomicAdd(&sh_gt[k % h], gt); atomicAdd(&sh_eq[k % h], eq); }
@@ -555,26 +648,28 @@ __global__ __launch_bounds__(256) void emit_write_kernel(
       }
     } else {
       // a plateau: stream the buckets, a wavefront per block
+      WaveHist wh(lh2);
+      int nfirst = 0, ncount = 0;
+      if (wv < nchunks) bucket_of(tb, (size_t)(cfirst + wv) * h + c, d1, nfirst, ncount);
       for (int k = wv; k < nchunks; k += 4) {
         const size_t kb = (size_t)(cfirst + k) * h + c;
-        int first, count;
-        bucket_of(tb, kb, d1, first, count);
-        const unsigned short *ent = tb.entries + kb * ENT_PER_BLOCK + first;
-        for (int i = lane; i < count; i += 64) atomicAdd(&lh2[ent[i] & 1023u], 1u);
+        const int first = nfirst, count = ncount;
+        if (k + 4 < nchunks) bucket_of(tb, (size_t)(cfirst + k + 4) * h + c, d1, nfirst, ncount);
+        for_bucket(tb.entries + kb * ENT_PER_BLOCK, first, count, wh);
       }
+      wh.flush();
       __syncthreads();
       locate_last(lh2, r1, d2, ties, sh);
+      CountAbove ca(d2);
+      if (wv < chunk) bucket_of(tb, (size_t)(cfirst + wv) * h + c, d1, nfirst, ncount);
       for (int k = wv; k < chunk; k += 4) {
         const size_t kb = (size_t)(cfirst + k) * h + c;
-        int first, count;
-        bucket_of(tb, kb, d1, first, count);
-        const unsigned short *ent = tb.entries + kb * ENT_PER_BLOCK + first;
-        for (int i = lane; i < count; i += 64) {
-          const unsigned v = ent[i] & 1023u;
-          pg += v > d2;
-          pe += v == d2;
-        }
+        const int first = nfirst, count = ncount;
+        if (k + 4 < chunk) bucket_of(tb, (size_t)(cfirst + k + 4) * h + c, d1, nfirst, ncount);
+        for_bucket(tb.entries + kb * ENT_PER_BLOCK, first, count, ca);
       }
+      pg += ca.gt;
+      pe += ca.eq;
     }
     thr = (d0 << 21) | (d1 << 10) | d2;
   }

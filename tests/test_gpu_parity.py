@@ -204,7 +204,7 @@ def _alloc_select(scores_np, w, B, alpha):
 
 
 @pytest.mark.parametrize("case", ["random", "quantised", "all_equal", "zeros_and_spikes", "plateaus",
-                                  "one_narrow_band", "long_bucket_in_one_block"])
+                                  "one_narrow_band", "long_bucket_in_one_block", "runs_in_one_band"])
 @pytest.mark.parametrize("alpha", [0.0, 0.2, 1.0])
 def test_allocate_select_bit_exact_on_oracle_scores(case, alpha):
     _say(f"allocate/select {case} alpha {alpha}")
@@ -224,6 +224,14 @@ def test_allocate_select_bit_exact_on_oracle_scores(case, alpha):
         # far more prefix-sharing elements than a finishing block holds at once
         base = np.array([0.3], np.float32).view(np.uint32)[0] & ~np.uint32(1023)
         s = (base + rng.integers(0, 1024, (h, n)).astype(np.uint32)).view(np.float32)
+    elif case == "runs_in_one_band":
+        # the same band, but in runs of one value, 1 to 700 positions long: stretches where whole
+        # wavefronts read one last digit call after call, stretches where only some lanes' eight
+        # entries agree, and value changes in between
+        base = np.array([0.3], np.float32).view(np.uint32)[0] & ~np.uint32(1023)
+        lens = rng.integers(1, 700, h * n) ** rng.integers(0, 2, h * n)
+        vals = np.repeat(rng.integers(0, 1024, h * n), lens)[:h * n].reshape(h, n)
+        s = (base + vals.astype(np.uint32)).view(np.float32)
     elif case == "long_bucket_in_one_block":
         # few prefix-sharing elements overall, but 1500 of them inside one block of 4096 positions
         s = (rng.random((h, n)) ** 8).astype(np.float32)
