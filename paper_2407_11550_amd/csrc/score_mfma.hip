@@ -415,8 +415,10 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // front of every MFMA (the first share covers the wait for the tile's LDS operands), and a scheduling fence after every share so that the order survives: an MFMA
   // runs for tens of cycles in the matrix core while the wavefront goes on issuing vector
   // instructions, but only if vector instructions follow it in program order.
-  auto fused_tile = [&](const bf16x8 (&kf)[KS], floatx16 (&accn)[MB], floatx16 (&acc)[MB], int tile) {
+  auto fused_tile = [&](const bf16x8 (&kf)[KS], floatx16 (&accn)[MB], floatx16 (&acc)[MB], int tile,
+                        auto &&between) {
     constexpr int SLOTS = MB * KS;               // matrix instructions per tile
+    constexpr int BETWEEN_SLOT = 6;              // between() runs after this slot's matrix instruction
     constexpr int VALS = MB * 16;                // products of the previous tile per lane
     floatx16 a[MB];
 #pragma unroll
@@ -442,6 +444,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
             sum[v / 16] += fast_exp2(fmaf(acc[v / 16][v % 16], c_log2, -rm[v / 16]));
           a[mb] = mfma16<F16>(kf[s], qf[mb][s], a[mb]);
           __builtin_amdgcn_sched_barrier(0);
+          if (slot == BETWEEN_SLOT) { between(); __builtin_amdgcn_sched_barrier(0); }
         }
       }
       bool bad = false;
@@ -477,6 +480,7 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
           }
           a[mb] = mfma16<F16>(kf[s], qf[mb][s], a[mb]);
           __builtin_amdgcn_sched_barrier(0);
+          if (slot == BETWEEN_SLOT) { between(); __builtin_amdgcn_sched_barrier(0); }
         }
       }
 #pragma unroll
@@ -486,21 +490,30 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
       }
       have_ref = true;
     } else {
-      float sum = 0.0f;
+      // The exponentials end two slots early, so that the exchange between the lane halves
+      // travels through the LDS crossbar while the last two matrix instructions are issued.
+      constexpr int ESLOTS = SLOTS - 2;
+      float sum = 0.0f, other = 0.0f;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
           const int slot = s * MB + mb;
+          if (slot < ESLOTS) {
 #pragma unroll
-          for (int v = slot * VALS / SLOTS; v < (slot + 1) * VALS / SLOTS; ++v)
-            sum += fast_exp2(fmaf(acc[v / 16][v % 16], c_log2, -l2[v / 16][v % 16]));
+            for (int v = slot * VALS / ESLOTS; v < (slot + 1) * VALS / ESLOTS; ++v)
+              sum += fast_exp2(fmaf(acc[v / 16][v % 16], c_log2, -l2[v / 16][v % 16]));
+          } else if (slot == ESLOTS) {
+            other = __shfl_xor(sum, 32);
+          }
           a[mb] = mfma16<F16>(qf[mb][s], kf[s], a[mb]);
           __builtin_amdgcn_sched_barrier(0);
+          if (slot == BETWEEN_SLOT) { between(); __builtin_amdgcn_sched_barrier(0); }
         }
       }
-      sum += __shfl_xor(sum, 32);
-      if (half == 0) sh_part[rs][tile * TILE + l32] = sum;   // key k0 + tile*TILE + l32
+      sum += other;
+      // key k0 + tile*TILE + l32; both lane halves hold the same sum and store it (no branch)
+      sh_part[rs][tile * TILE + l32] = sum;
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) accn[mb] = a[mb];
@@ -518,14 +531,24 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < KS; ++s) kf[s] = as_bf16(buf[rd_off + s * 2]);
     // always issued (the last iterations re-read the final set): a conditional load would make
-    // the compiler wait for every outstanding load before the stores below
-    load_set(ga, phys(min(it + DEPTH, iters - 1)));
+    // the compiler wait for every outstanding load before the stores below.  With eight
+    // wavefronts, all of a compute unit's wavefronts leave the barrier together and nothing
+    // overlaps with the scalar address arithmetic of the load at the top of a tile; the weights
+    // sweep issues it between the tile's matrix instructions instead (measured on the 512-row
+    // shape: 153.5 -> 150.2 us; the statistics sweep, which has less other work between its
+    // matrix instructions to hide a late load behind, lost 7 us and keeps it at the top).
+    constexpr bool LOAD_BETWEEN = NW == 8 && PASS == 2;
+    auto ask = [&]() { load_set(ga, phys(min(it + DEPTH, iters - 1))); };
+    auto between = [&]() {
+      if constexpr (LOAD_BETWEEN) ask();
+    };
+    if constexpr (!LOAD_BETWEEN) ask();
     const int tile = phys(it) * KG + kg;
     const bool have = tile < ntiles;
     if (!PR && have && prev_tile >= 0 && is_full(prev_tile)) {
       // the common case, straight-line: products of this tile, arithmetic of the previous one
       floatx16 accn[MB];
-      fused_tile(kf, accn, accp, prev_tile);
+      fused_tile(kf, accn, accp, prev_tile, between);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) accp[mb] = accn[mb];
       prev_tile = tile;
@@ -535,12 +558,13 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
         else epilogue(std::true_type{}, accp, prev_tile);
       }
       prev_tile = -1;
+      between();
       if (have) {
         mma(kf, accp);
         prev_tile = tile;
       }
     }
-    if (it + 1 < iters) store_set(gb, (it + 1) & 1);
+    store_set(gb, (it + 1) & 1);               // (after the last iteration nobody reads it: no branch)
     __syncthreads();
   };
   {
@@ -690,7 +714,7 @@ hipError_t run_mfma_d(const MfmaVariant &v, const SeqTab &st, const Dims &dm, co
   ADAKV_MFMA_CASE(2, 2, 2, 1024)
   ADAKV_MFMA_CASE(2, 2, 2, 512)
   ADAKV_MFMA_CASE(2, 4, 1, 1024)
-  if constexpr (D == 128) { ADAKV_MFMA_CASE(2, 8, 1, 1024) }
+  if constexpr (D == 128) { ADAKV_MFMA_CASE(2, 8, 1, 2048) }
   else { ADAKV_MFMA_CASE(4, 4, 1, 1024) }
 #undef ADAKV_MFMA_CASE
   return hipErrorInvalidValue;                 // a variant nobody instantiated
@@ -722,8 +746,11 @@ MfmaVariant choose_mfma_variant(const SeqTab &st, const Dims &dm) {
     v = {2, 2, 2, chunk, false, false};
   } else if (R <= 256) v = {2, 4, 1, 1024, false, false};
   // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
-  // a tile half the loads, so four wavefronts of 128 rows
-  else if (dm.d == 128) v = {2, 8, 1, 1024, false, false};
+  // a tile half the loads, so four wavefronts of 128 rows.  Eight wavefronts fill a compute unit,
+  // so nothing overlaps with a workgroup's set-up and epilogue (about 4 and 7 us in the two
+  // sweeps): chunks of 2048 keys halve their number (measured on 131072 keys: 157 -> 145 and
+  // 175 -> 155 us for the two sweeps).
+  else if (dm.d == 128) v = {2, 8, 1, 2048, false, false};
   else v = {4, 4, 1, 1024, false, false};
   // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a head has so many
   // (chunks x rows) that every workgroup re-reading them would cost more than a kernel, and it

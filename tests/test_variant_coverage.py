@@ -42,7 +42,7 @@ def test_gpu_shapes_reach_every_scoring_variant(lib):
         for mb, rs, kg, chunk in ((1, 1, 4, 2048), (2, 1, 4, 2048), (2, 2, 2, 512), (2, 2, 2, 1024),
                                   (2, 2, 2, 2048), (2, 4, 1, 1024)):
             want.add((dt, d, mb, rs, kg, chunk))
-        want.add((dt, d, 2, 8, 1, 1024) if d == 128 else (dt, d, 4, 4, 1, 1024))
+        want.add((dt, d, 2, 8, 1, 2048) if d == 128 else (dt, d, 4, 4, 1, 1024))
     # the same instantiations once more for the other order of pooling and averaging
     want |= {("pool-first",) + v for v in set(want)}
     for d in (64, 128):
