@@ -106,7 +106,7 @@ def variant_shapes():
         (18, 2, 128, 64, 3, 800, 90, torch.float16),
         (8, 2, 128, 32, 71, 3000, 150, torch.bfloat16),   # pool radius beyond the fused halo
         (8, 2, 64, 32, 67, 2600, 150, torch.float16),
-        (16, 2, 128, 64, 7, 17500, 300, torch.float16),   # 512 rows x 18 chunks: statistics kernel
+        (16, 2, 128, 64, 7, 35100, 300, torch.float16),   # 512 rows x 18 chunks: statistics kernel
     ]
     return out
 
