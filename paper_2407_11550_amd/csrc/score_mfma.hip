@@ -576,33 +576,13 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   // scalar and 6 to 9 branches, against the tile's own 16 + 96.
   constexpr bool PAIRS = !PR && DEPTH == 2 && NW == 8;   // (the smaller shapes are bound by memory and would pay with registers)
   const int plain_sets = min(ntiles / KG, (n - k0) / (KG * TILE));   // sets [0, plain_sets): every tile there and full
-  // sets [inner_lo, inner_hi): all rows inside what somebody reads, so that the load needs no clamps
-  const int set_rows = SETT * tstep;
-  const int inner_lo = (max(need_lo - k0, 0) + set_rows - 1) / set_rows;
-  const int inner_hi = (need_hi - k0 + 1) / set_rows;
-  const size_t set_bytes = (size_t)set_rows * tok_bytes;
-  const char *set0 = kbase + (size_t)k0 * tok_bytes;
-  unsigned ld_off[LDPT];                               // the thread's place inside a set, in bytes
-#pragma unroll
-  for (int i = 0; i < LDPT; ++i) ld_off[i] = (unsigned)ld_rel[i] * (unsigned)tok_bytes + col_bytes;
-  auto load_inner = [&](u32x4 (&g)[LDPT], int set) {
-    const char *sb = set0 + (size_t)set * set_bytes;
-#pragma unroll
-    for (int i = 0; i < LDPT; ++i) g[i] = *reinterpret_cast<const u32x4 *>(sb + ld_off[i]);
-  };
-  // the set that follows set p in this workgroup's order (phys(it + 1) from phys(it))
-  auto next_set = [&](int p) {
-    if (INTER) return p + nch;
-    if (PASS == 2) return p == 0 ? iters - 1 : p - 1;
-    return p + 1 == iters ? 0 : p + 1;
-  };
-  // p0, p1: the pair's sets; p2, p3: the two after them, whose rows are asked for (inner sets)
-  auto pair = [&](int p0, int p1, int p2, int p3) {
+  auto pair = [&](int it) {
     constexpr bool LOAD_BETWEEN = NW == 8 && PASS == 2;
     bf16x8 kf[KS];
     floatx16 accq[MB];
-    auto ask0 = [&]() { load_inner(g[0], p2); };
-    auto ask1 = [&]() { load_inner(g[1], p3); };
+    const int t0 = phys(it) * KG + kg, t1 = phys(it + 1) * KG + kg;
+    auto ask0 = [&]() { load_set(g[0], phys(min(it + 2, iters - 1))); };
+    auto ask1 = [&]() { load_set(g[1], phys(min(it + 3, iters - 1))); };
     auto nothing = [&]() {};
 #pragma unroll
     for (int s = 0; s < KS; ++s) kf[s] = as_bf16(kt[0][rd_off + s * 2]);
@@ -617,37 +597,27 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < KS; ++s) kf[s] = as_bf16(kt[1][rd_off + s * 2]);
     if constexpr (LOAD_BETWEEN) {
-      fused_tile(kf, accp, accq, p0 * KG + kg, ask1);
+      fused_tile(kf, accp, accq, t0, ask1);
     } else {
       ask1();
-      fused_tile(kf, accp, accq, p0 * KG + kg, nothing);
+      fused_tile(kf, accp, accq, t0, nothing);
     }
     store_set(g[0], 0);
     __syncthreads();
-    prev_tile = p1 * KG + kg;
+    prev_tile = t1;
   };
   {
     store_set(g[0], 0);
     __syncthreads();
     int it = 0;
     while (it < iters) {
-      bool paired = false;
-      if (PAIRS && !(it & 1) && it + 4 <= iters && prev_tile >= 0 && is_full(prev_tile)) {
-        int p0 = phys(it), p1 = next_set(p0), p2 = next_set(p1), p3 = next_set(p2);
-        auto fits = [&]() {
-          return p0 < plain_sets && p1 < plain_sets && p2 >= inner_lo && p2 < inner_hi && p3 >= inner_lo && p3 < inner_hi;
-        };
-        while (it + 4 <= iters && fits()) {
-          pair(p0, p1, p2, p3);
+      if (PAIRS && !(it & 1) && it + 2 <= iters && prev_tile >= 0 && is_full(prev_tile) &&
+          phys(it) < plain_sets && phys(it + 1) < plain_sets) {
+        do {
+          pair(it);
           it += 2;
-          p0 = p2;
-          p1 = p3;
-          p2 = next_set(p3);
-          p3 = next_set(p2);
-          paired = true;
-        }
-      }
-      if (!paired) {
+        } while (it + 2 <= iters && phys(it) < plain_sets && phys(it + 1) < plain_sets);
+      } else {
         if (it & 1) step(it, g[1], g[0]);
         else step(it, g[0], g[1]);
         ++it;
