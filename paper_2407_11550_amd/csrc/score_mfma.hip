@@ -609,18 +609,26 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   {
     store_set(g[0], 0);
     __syncthreads();
-    int it = 0;
-    while (it < iters) {
-      if (PAIRS && !(it & 1) && it + 2 <= iters && prev_tile >= 0 && is_full(prev_tile) &&
-          phys(it) < plain_sets && phys(it + 1) < plain_sets) {
-        do {
-          pair(it);
-          it += 2;
-        } while (it + 2 <= iters && phys(it) < plain_sets && phys(it + 1) < plain_sets);
-      } else {
-        if (it & 1) step(it, g[1], g[0]);
-        else step(it, g[0], g[1]);
-        ++it;
+    if constexpr (PAIRS) {
+      int it = 0;
+      while (it < iters) {
+        if (!(it & 1) && it + 2 <= iters && prev_tile >= 0 && is_full(prev_tile) &&
+            phys(it) < plain_sets && phys(it + 1) < plain_sets) {
+          do {
+            pair(it);
+            it += 2;
+          } while (it + 2 <= iters && phys(it) < plain_sets && phys(it + 1) < plain_sets);
+        } else {
+          if (it & 1) step(it, g[1], g[0]);
+          else step(it, g[0], g[1]);
+          ++it;
+        }
+      }
+    } else {
+      for (int it = 0; it < iters; it += DEPTH) {
+#pragma unroll
+        for (int j = 0; j < DEPTH; ++j)
+          if (it + j < iters) step(it + j, g[j], g[(j + 1) % DEPTH]);
       }
     }
     if (prev_tile >= 0) {
