@@ -28,6 +28,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published peak
+MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 / fp16 MFMA, published peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 PROFILES = os.path.join(ROOT, "profiles")
 
@@ -335,6 +336,16 @@ def main():
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "traffic_source": f"profiles/{wl.name}_hbm_traffic.md" if traffic else None,
                 "algorithmic_bytes": dom_bytes, "avg_us": round(dom_us, 2)}
+    # A scoring sweep does 2 g w d h flops per token on h d 2 bytes of K: g w flops per byte.  Past
+    # the machine balance (dense 16-bit MFMA peak over HBM peak, 312 flops per byte) the sweep is
+    # bound by the matrix cores and is priced against their peak; the HBM figure stays beside it.
+    if (dominant in ("score_stats_mfma", "score_weights_mfma") and not str(wl.dtype).endswith("float32")
+            and wl.g * wl.w > MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)):
+        tflops = flops / (dom_us * 1e-6) / 1e12
+        roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(tflops, 1), "peak": MFMA_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(tflops / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
+                    "traffic_source": roofline["traffic_source"], "algorithmic_flops": flops,
+                    "algorithmic_bytes": dom_bytes, "hbm_frac": roofline["frac"], "avg_us": round(dom_us, 2)}
     # counter traffic of the whole step (every kernel of it, from the same summary) over the bytes
     # the path has to move: what is above 1 is re-read or scratch traffic
     step_traffic = (sum(per_kernel_traffic[k] for k in order) if per_kernel_traffic
