@@ -249,6 +249,30 @@ def test_allocate_select_bit_exact_on_oracle_scores(case, alpha):
         assert np.array_equal(idx, O.select(s, rb, w)), (case, B)
 
 
+@pytest.mark.parametrize("case", ["runs_in_one_band", "band_beside_random"])
+def test_allocate_select_plateaus_across_many_blocks(case):
+    """Plateaus over 37 blocks of 4096 positions per head: the finishing kernels stream more
+    blocks than they have wavefronts, so every wavefront looks a block ahead while it streams one
+    (with the 10007-position heads above no wavefront ever has a second block)."""
+    _say(f"allocate/select many blocks {case}")
+    rng = np.random.default_rng(5)
+    h, n, w = 3, 150001, 8
+    base = np.array([0.3], np.float32).view(np.uint32)[0] & ~np.uint32(1023)
+    if case == "runs_in_one_band":
+        lens = rng.integers(1, 5000, h * n) ** rng.integers(0, 2, h * n)
+        vals = np.repeat(rng.integers(0, 1024, h * n), lens)[:h * n].reshape(h, n)
+        s = (base + vals.astype(np.uint32)).view(np.float32)
+    else:
+        band = (base + rng.integers(0, 4, (h, n)).astype(np.uint32)).view(np.float32)
+        s = np.where(rng.random((h, n)) < 0.5, band, (rng.random((h, n)) ** 6).astype(np.float32))
+    for alpha, B in ((0.2, w * h + 5000), (0.0, w * h + h * n // 3), (1.0, w * h + h * n - 7)):
+        bud, cu, idx = _alloc_select(s, w, B, alpha)
+        rb, rcu = O.allocate(s, B, w, alpha)
+        assert np.array_equal(bud, rb), (case, alpha, B, bud, rb)
+        assert np.array_equal(cu, rcu)
+        assert np.array_equal(idx, O.select(s, rb, w)), (case, alpha, B)
+
+
 def test_select_with_zero_budget_heads_and_full_heads():
     _say("select zero/full budgets")
     rng = np.random.default_rng(4)
