@@ -122,12 +122,14 @@ def test_every_scoring_variant_matches_oracle(shape):
     _check_all(wl, q, K, V, out)
 
 
-def test_statistics_sweep_survives_logits_far_above_its_first_tile():
+@pytest.mark.parametrize("h_q, rs", [(8, "4"), (16, "8")])      # 256 and 512 rows per KV head
+def test_statistics_sweep_survives_logits_far_above_its_first_tile(h_q, rs):
     """The statistics sweep of the many-row shapes keeps the reference its first tile gave a row
     and only looks for a new maximum when a sum overflows.  Here the first 64 keys are tiny and
-    later keys give logits more than 128 powers of two above them, so that path is taken."""
-    _say("statistics sweep: overflow of the kept reference")
-    wl = synth.small_workload(8, 2, 128, 64, 7, 3000, 2 * 300, dtype=torch.bfloat16, seed=77)   # 256 rows per head
+    later keys give logits more than 128 powers of two above them, so that path is taken (in the
+    512-row shape from inside the loop of tile pairs)."""
+    _say(f"statistics sweep: overflow of the kept reference, {h_q} query heads")
+    wl = synth.small_workload(h_q, 2, 128, 64, 7, 3000, 2 * 300, dtype=torch.bfloat16, seed=77)
     q, K, V = synth.generate(wl, device=DEV)
     q = (q.float() * 4).to(torch.bfloat16)
     K = K.float()
@@ -137,7 +139,7 @@ def test_statistics_sweep_survives_logits_far_above_its_first_tile():
     logits = torch.einsum("hwd,nd->hwn", q[0, :4].float(), K[:3000, 0].float()) / 128 ** 0.5
     assert float((logits[:, :, 64:].amax(-1) - logits[:, :, :64].amax(-1)).max()) * 1.4427 > 128
     _, out = _run(wl, q, K, V)
-    assert adakv.describe(adakv.Layer.from_workload(wl))["rs"] == "4"
+    assert adakv.describe(adakv.Layer.from_workload(wl))["rs"] == rs
     _check_all(wl, q, K, V, out)
 
 
