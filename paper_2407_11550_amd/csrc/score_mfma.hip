@@ -92,7 +92,10 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   __shared__ float sh_part[PASS == 2 ? RS : 1][PASS == 2 ? CHUNK + 2 * HALO : 1];
   constexpr int NCOMB = NT > RPAD ? NT : RPAD;   // (thread slices) x (rows) of the statistics combination
   __shared__ float sh_cm[PASS == 2 ? NCOMB : 1], sh_cl[PASS == 2 ? NCOMB : 1];
-  __shared__ unsigned sh_hist[PASS == 2 ? RADIX_BINS : 1];   // first radix digits of the chunk's scores
+  // first radix digits of the chunk's scores: only needed once the tile loop is over, in the
+  // place of the K tiles (which leaves room for 4096-key chunks of eight row groups)
+  static_assert(sizeof(kt) >= RADIX_BINS * sizeof(unsigned), "the digit histogram must fit into the tile buffers");
+  unsigned *sh_hist = reinterpret_cast<unsigned *>(&kt[0][0]);
 
   const int tid = threadIdx.x, lane = tid & 63;
   // Pipeline mode: the statistics sweep clears the Top-k histograms (they are first touched by
@@ -100,9 +103,6 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
   if (PASS == 1 && tc.zero_begin) {
     for (unsigned i = blockIdx.x * NT + tid; i < tc.zero_words; i += gridDim.x * NT)
       tc.zero_begin[i] = 0u;
-  }
-  if (PASS == 2 && tc.hist0) {
-    for (int i = tid; i < RADIX_BINS; i += NT) sh_hist[i] = 0u;
   }
 
   // the wavefront index is the same in all lanes: telling the compiler keeps everything derived
@@ -669,6 +669,9 @@ __global__ __launch_bounds__(64 * RS * KG) void score_mfma_kernel(
     // stride 1, same length, window clipped to the sequence (Section 4.1: kernel 7)
     const float inv = 1.0f / (float)R;
     const int span = k1 - k0;
+    if (tc.hist0) {                              // (the barrier above was the last use of the K tiles)
+      for (int i = tid; i < RADIX_BINS; i += NT) sh_hist[i] = 0u;
+    }
     for (int j = tid; j < span; j += NT) {
       float tot = 0.0f;
 #pragma unroll
@@ -770,7 +773,7 @@ hipError_t run_mfma_d(const MfmaVariant &v, const SeqTab &st, const Dims &dm, co
   ADAKV_MFMA_CASE(2, 2, 2, 1024)
   ADAKV_MFMA_CASE(2, 2, 2, 512)
   ADAKV_MFMA_CASE(2, 4, 1, 1024)
-  if constexpr (D == 128) { ADAKV_MFMA_CASE(2, 8, 1, 2048) }
+  if constexpr (D == 128) { ADAKV_MFMA_CASE(2, 8, 1, 2048) ADAKV_MFMA_CASE(2, 8, 1, 4096) }
   else { ADAKV_MFMA_CASE(4, 4, 1, 1024) }
 #undef ADAKV_MFMA_CASE
   return hipErrorInvalidValue;                 // a variant nobody instantiated
@@ -806,7 +809,13 @@ MfmaVariant choose_mfma_variant(const SeqTab &st, const Dims &dm) {
   // so nothing overlaps with a workgroup's set-up and epilogue (about 4 and 7 us in the two
   // sweeps): chunks of 2048 keys halve their number (measured on 131072 keys: 157 -> 145 and
   // 175 -> 155 us for the two sweeps).
-  else if (dm.d == 128) v = {2, 8, 1, 2048, false, false};
+  else if (dm.d == 128) {
+    long long keys = 0;
+    for (int b = 0; b < st.batch; ++b) keys += st.n[b];
+    // 4096 keys when that still gives every compute unit a workgroup (one round instead of two)
+    const long long wg4096 = (keys / 4096 + st.batch) * dm.h_kv;
+    v = {2, 8, 1, wg4096 >= 256 ? 4096 : 2048, false, false};
+  }
   else v = {4, 4, 1, 1024, false, false};
   // Fused forms: sweep 2 combines sweep 1's partial statistics itself unless a head has so many
   // (chunks x rows) that every workgroup re-reading them would cost more than a kernel, and it

@@ -122,6 +122,22 @@ def test_every_scoring_variant_matches_oracle(shape):
     _check_all(wl, q, K, V, out)
 
 
+SHAPE_512_ROWS_4096_KEYS = (256, 32, 128, 64, 7, [4200, 33, 64, 31, 50, 40, 35, 47])   # 8 sequences x 32 KV heads
+
+
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
+def test_512_rows_with_4096_key_chunks(dt):
+    """The 512-row shape takes 4096-key chunks as soon as that still gives 256 workgroups; here
+    eight sequences x 32 KV heads do, one sequence being longer than a chunk and ragged."""
+    _say(f"512 rows, 4096-key chunks, {dt}")
+    h_q, h, d, w, k, n = SHAPE_512_ROWS_4096_KEYS
+    wl = synth.small_workload(h_q, h, d, w, k, n, [h * (w + max(1, nb // 10)) for nb in n], dtype=dt, seed=41)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer, out = _run(wl, q, K, V)
+    assert adakv.describe(layer)["chunk"] == "4096" and adakv.describe(layer)["rs"] == "8"
+    _check_all(wl, q, K, V, out)
+
+
 @pytest.mark.parametrize("h_q, rs", [(8, "4"), (16, "8")])      # 256 and 512 rows per KV head
 def test_statistics_sweep_survives_logits_far_above_its_first_tile(h_q, rs):
     """The statistics sweep of the many-row shapes keeps the reference its first tile gave a row
@@ -621,6 +637,8 @@ POOL_FIRST_CASES = [
 # variant_shapes() that are scored on the matrix cores, with their own pool kernels (3 to 9)
 POOL_FIRST_CASES += [(h_q, h, d, w, k, [n], dt, False) for h_q, h, d, w, k, n, _, dt in variant_shapes()
                      if h_q // h * w <= 512 and k // 2 <= 7]
+# ... and the 512-row shape in 4096-key chunks
+POOL_FIRST_CASES += [SHAPE_512_ROWS_4096_KEYS + (dt, False) for dt in (torch.bfloat16, torch.float16)]
 
 
 @pytest.mark.parametrize("case", POOL_FIRST_CASES,
