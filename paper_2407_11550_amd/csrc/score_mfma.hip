@@ -769,6 +769,7 @@ hipError_t run_mfma_d(const MfmaVariant &v, const SeqTab &st, const Dims &dm, co
   }
   ADAKV_MFMA_CASE(1, 1, 4, 2048)
   ADAKV_MFMA_CASE(2, 1, 4, 2048)
+  ADAKV_MFMA_CASE(2, 2, 2, 4096)
   ADAKV_MFMA_CASE(2, 2, 2, 2048)
   ADAKV_MFMA_CASE(2, 2, 2, 1024)
   ADAKV_MFMA_CASE(2, 2, 2, 512)
@@ -801,7 +802,14 @@ MfmaVariant choose_mfma_variant(const SeqTab &st, const Dims &dm) {
     long long keys = 0;
     for (int b = 0; b < st.batch; ++b) keys += st.n[b];
     const long long wg2048 = (keys / 2048 + st.batch) * dm.h_kv;
-    const int chunk = wg2048 >= CHUNK_SWITCH_WGS ? 2048 : 2 * wg2048 >= CHUNK_SWITCH_WGS ? 1024 : 512;
+    // 4096 keys when that alone nearly fills the 512 workgroups the chip holds at a time (seven
+    // eighths of them): one round of long workgroups instead of almost two of short ones
+    // (`llama8b_ragged`: 904 workgroups of 2048 keys or 472 of 4096, 279 -> 271 us per layer)
+    long long wg4096 = 0;
+    for (int b = 0; b < st.batch; ++b) wg4096 += (st.n[b] + 4095) / 4096;
+    wg4096 *= dm.h_kv;
+    const int chunk = 8 * wg4096 >= 7 * CHUNK_SWITCH_WGS ? 4096
+                      : wg2048 >= CHUNK_SWITCH_WGS ? 2048 : 2 * wg2048 >= CHUNK_SWITCH_WGS ? 1024 : 512;
     v = {2, 2, 2, chunk, false, false};
   } else if (R <= 256) v = {2, 4, 1, 1024, false, false};
   // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and

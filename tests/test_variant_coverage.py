@@ -21,6 +21,8 @@ def _variants_reached():
     layers += [synth.workload(nm) for nm in ("tiny", "llama8b_32k", "llama8b_128k", "llama8b_ragged", "llama70b_128k")]
     h_q, h, d, w, k, n = G.SHAPE_512_ROWS_4096_KEYS
     layers += [synth.small_workload(h_q, h, d, w, k, n, [h * (w + 1)] * len(n), dtype=dt) for dt in (torch.bfloat16, torch.float16)]
+    layers += [synth.small_workload(h_q, h, d, w, k, n, [h * (w + 1)] * len(n), dtype=dt)
+               for h_q, h, d, w, k, n in G.SHAPES_128_ROWS_4096_KEYS for dt in (torch.bfloat16, torch.float16)]
     described = [adakv.describe(adakv.Layer.from_workload(wl)) for wl in layers]
     for h_q, h, d, w, k, n, dt, _ in G.POOL_FIRST_CASES:
         wl = synth.small_workload(h_q, h, d, w, k, n, [h * (w + max(1, nb // 10)) for nb in n], dtype=dt)
@@ -42,7 +44,7 @@ def test_gpu_shapes_reach_every_scoring_variant(lib):
     want = set()
     for dt, d in itertools.product(("bf16", "fp16"), (64, 128)):
         for mb, rs, kg, chunk in ((1, 1, 4, 2048), (2, 1, 4, 2048), (2, 2, 2, 512), (2, 2, 2, 1024),
-                                  (2, 2, 2, 2048), (2, 4, 1, 1024)):
+                                  (2, 2, 2, 2048), (2, 2, 2, 4096), (2, 4, 1, 1024)):
             want.add((dt, d, mb, rs, kg, chunk))
         if d == 128:
             want |= {(dt, d, 2, 8, 1, 2048), (dt, d, 2, 8, 1, 4096)}
