@@ -782,6 +782,35 @@ hipError_t run_mfma_d(const MfmaVariant &v, const SeqTab &st, const Dims &dm, co
 
 }  // namespace
 
+// The instantiations are split over four translation units by head dimension and element type,
+// so that they compile side by side: ADAKV_MFMA_PART = 1 .. 4 builds one quarter (part 1 also the
+// host functions below), 0 or undefined everything.
+#ifndef ADAKV_MFMA_PART
+#define ADAKV_MFMA_PART 0
+#endif
+#define ADAKV_MFMA_ARGS                                                                          \
+  const MfmaVariant &v, const SeqTab &st, const Dims &dm, const void *q, const void *K,          \
+      const float *row_lse, float *scores, char *ws, const ScorePlan &pl, const TopkCarry &tc,   \
+      bool pool_rows, hipStream_t s
+hipError_t run_mfma_d64_bf16(ADAKV_MFMA_ARGS);
+hipError_t run_mfma_d64_fp16(ADAKV_MFMA_ARGS);
+hipError_t run_mfma_d128_bf16(ADAKV_MFMA_ARGS);
+hipError_t run_mfma_d128_fp16(ADAKV_MFMA_ARGS);
+#if ADAKV_MFMA_PART == 0 || ADAKV_MFMA_PART == 1
+hipError_t run_mfma_d64_bf16(ADAKV_MFMA_ARGS) { return run_mfma_d<64, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s); }
+#endif
+#if ADAKV_MFMA_PART == 0 || ADAKV_MFMA_PART == 2
+hipError_t run_mfma_d64_fp16(ADAKV_MFMA_ARGS) { return run_mfma_d<64, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s); }
+#endif
+#if ADAKV_MFMA_PART == 0 || ADAKV_MFMA_PART == 3
+hipError_t run_mfma_d128_bf16(ADAKV_MFMA_ARGS) { return run_mfma_d<128, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s); }
+#endif
+#if ADAKV_MFMA_PART == 0 || ADAKV_MFMA_PART == 4
+hipError_t run_mfma_d128_fp16(ADAKV_MFMA_ARGS) { return run_mfma_d<128, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s); }
+#endif
+#undef ADAKV_MFMA_ARGS
+
+#if ADAKV_MFMA_PART == 0 || ADAKV_MFMA_PART == 1
 // 16-bit inputs with at most 512 window rows per KV head (g*w); anything else takes the FMA path.
 bool mfma_path_supported(const Dims &dm, int dtype) {
   return (dtype == ADAKV_BF16 || dtype == ADAKV_FP16) && dm.g * dm.w <= 512 && (dm.d == 64 || dm.d == 128) &&
@@ -843,10 +872,10 @@ hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, int dtype, const 
                              hipStream_t s) {
   const MfmaVariant v = choose_mfma_variant(st, dm);
   if (dtype == ADAKV_FP16)
-    return dm.d == 64 ? run_mfma_d<64, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s)
-                      : run_mfma_d<128, true>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s);
-  return dm.d == 64 ? run_mfma_d<64, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s)
-                    : run_mfma_d<128, false>(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s);
+    return dm.d == 64 ? run_mfma_d64_fp16(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s)
+                      : run_mfma_d128_fp16(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s);
+  return dm.d == 64 ? run_mfma_d64_bf16(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s)
+                    : run_mfma_d128_bf16(v, st, dm, q, K, row_lse, scores, ws, pl, tc, pool_rows, s);
 }
 
 // The printed order of Alg. 2 l.4 (pool every row, then average) runs on the matrix cores as long
@@ -854,5 +883,6 @@ hipError_t launch_score_mfma(const SeqTab &st, const Dims &dm, int dtype, const 
 bool mfma_pool_rows_supported(const Dims &dm, int dtype) {
   return mfma_path_supported(dm, dtype) && dm.pool_k / 2 <= MFMA_POOL_ROWS_MAX_RADIUS;
 }
+#endif  // ADAKV_MFMA_PART == 0 || ADAKV_MFMA_PART == 1
 
 }  // namespace adakv
