@@ -773,6 +773,7 @@ hipError_t run_mfma_d(const MfmaVariant &v, const SeqTab &st, const Dims &dm, co
   ADAKV_MFMA_CASE(2, 2, 2, 2048)
   ADAKV_MFMA_CASE(2, 2, 2, 1024)
   ADAKV_MFMA_CASE(2, 2, 2, 512)
+  ADAKV_MFMA_CASE(2, 4, 1, 2048)
   ADAKV_MFMA_CASE(2, 4, 1, 1024)
   if constexpr (D == 128) { ADAKV_MFMA_CASE(2, 8, 1, 2048) ADAKV_MFMA_CASE(2, 8, 1, 4096) }
   else { ADAKV_MFMA_CASE(4, 4, 1, 1024) }
@@ -840,7 +841,13 @@ MfmaVariant choose_mfma_variant(const SeqTab &st, const Dims &dm) {
     const int chunk = 8 * wg4096 >= 7 * CHUNK_SWITCH_WGS ? 4096
                       : wg2048 >= CHUNK_SWITCH_WGS ? 2048 : 2 * wg2048 >= CHUNK_SWITCH_WGS ? 1024 : 512;
     v = {2, 2, 2, chunk, false, false};
-  } else if (R <= 256) v = {2, 4, 1, 1024, false, false};
+  } else if (R <= 256) {
+    // (the same rule one chunk length down: these workgroups carry twice the rows)
+    long long wg2048 = 0;
+    for (int b = 0; b < st.batch; ++b) wg2048 += (st.n[b] + 2047) / 2048;
+    wg2048 *= dm.h_kv;
+    v = {2, 4, 1, 8 * wg2048 >= 7 * CHUNK_SWITCH_WGS ? 2048 : 1024, false, false};
+  }
   // 512 rows: eight wavefronts of 64 rows; with d = 64 a row block needs half the registers and
   // a tile half the loads, so four wavefronts of 128 rows.  Eight wavefronts fill a compute unit,
   // so nothing overlaps with a workgroup's set-up and epilogue (about 4 and 7 us in the two

@@ -126,6 +126,23 @@ SHAPE_512_ROWS_4096_KEYS = (256, 32, 128, 64, 7, [4200, 33, 64, 31, 50, 40, 35, 
 SHAPES_128_ROWS_4096_KEYS = [(64, 64, d, 100, 7, [4200, 33, 64, 31, 50, 40, 35]) for d in (64, 128)]   # 7 x 64 KV heads
 
 
+SHAPES_256_ROWS_2048_KEYS = [(128, 64, d, 100, 7, [2300, 33, 64, 31, 50, 40, 35]) for d in (64, 128)]   # 200 rows per head
+
+
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("shape", SHAPES_256_ROWS_2048_KEYS, ids=lambda s_: "d%d" % s_[2])
+def test_256_rows_with_2048_key_chunks(shape, dt):
+    """The 256-row kernels take 2048-key chunks under the same rule (448 workgroups or more)."""
+    _say(f"256 rows, 2048-key chunks, {shape} {dt}")
+    h_q, h, d, w, k, n = shape
+    wl = synth.small_workload(h_q, h, d, w, k, n, [h * (w + max(1, nb // 10)) for nb in n], dtype=dt, seed=45)
+    q, K, V = synth.generate(wl, device=DEV)
+    layer, out = _run(wl, q, K, V)
+    desc = adakv.describe(layer)
+    assert desc["chunk"] == "2048" and (desc["mb"], desc["rs"], desc["kg"]) == ("2", "4", "1")
+    _check_all(wl, q, K, V, out)
+
+
 @pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("shape", SHAPES_128_ROWS_4096_KEYS, ids=lambda s_: "d%d" % s_[2])
 def test_128_rows_with_4096_key_chunks(shape, dt):
@@ -655,7 +672,8 @@ POOL_FIRST_CASES += [(h_q, h, d, w, k, [n], dt, False) for h_q, h, d, w, k, n, _
                      if h_q // h * w <= 512 and k // 2 <= 7]
 # ... and the 512-row shape in 4096-key chunks
 POOL_FIRST_CASES += [SHAPE_512_ROWS_4096_KEYS + (dt, False) for dt in (torch.bfloat16, torch.float16)]
-POOL_FIRST_CASES += [shape + (dt, False) for shape in SHAPES_128_ROWS_4096_KEYS for dt in (torch.bfloat16, torch.float16)]
+POOL_FIRST_CASES += [shape + (dt, False) for shape in SHAPES_128_ROWS_4096_KEYS + SHAPES_256_ROWS_2048_KEYS
+                     for dt in (torch.bfloat16, torch.float16)]
 
 
 @pytest.mark.parametrize("case", POOL_FIRST_CASES,

@@ -78,9 +78,9 @@ def test_two_wavefronts_per_simd_where_the_layout_counts_on_them(score_kernels):
             continue
         assert md["vgpr"] + md["agpr"] <= 256, ((d, mb, rs, kg, chunk, sweep, f16), md)
         checked += 1
-    # types x sweeps x (d = 128: four chunk lengths, 256 rows, 512 rows with two chunk lengths;
-    # d = 64: the first five)
-    assert checked == 2 * 2 * (7 + 5)
+    # types x sweeps x (d = 128: four chunk lengths, 256 rows and 512 rows with two each;
+    # d = 64: the first six)
+    assert checked == 2 * 2 * (8 + 6)
 
 
 def test_no_scoring_kernel_spills(score_kernels):

@@ -22,7 +22,8 @@ def _variants_reached():
     h_q, h, d, w, k, n = G.SHAPE_512_ROWS_4096_KEYS
     layers += [synth.small_workload(h_q, h, d, w, k, n, [h * (w + 1)] * len(n), dtype=dt) for dt in (torch.bfloat16, torch.float16)]
     layers += [synth.small_workload(h_q, h, d, w, k, n, [h * (w + 1)] * len(n), dtype=dt)
-               for h_q, h, d, w, k, n in G.SHAPES_128_ROWS_4096_KEYS for dt in (torch.bfloat16, torch.float16)]
+               for h_q, h, d, w, k, n in G.SHAPES_128_ROWS_4096_KEYS + G.SHAPES_256_ROWS_2048_KEYS
+               for dt in (torch.bfloat16, torch.float16)]
     described = [adakv.describe(adakv.Layer.from_workload(wl)) for wl in layers]
     for h_q, h, d, w, k, n, dt, _ in G.POOL_FIRST_CASES:
         wl = synth.small_workload(h_q, h, d, w, k, n, [h * (w + max(1, nb // 10)) for nb in n], dtype=dt)
@@ -44,7 +45,7 @@ def test_gpu_shapes_reach_every_scoring_variant(lib):
     want = set()
     for dt, d in itertools.product(("bf16", "fp16"), (64, 128)):
         for mb, rs, kg, chunk in ((1, 1, 4, 2048), (2, 1, 4, 2048), (2, 2, 2, 512), (2, 2, 2, 1024),
-                                  (2, 2, 2, 2048), (2, 2, 2, 4096), (2, 4, 1, 1024)):
+                                  (2, 2, 2, 2048), (2, 2, 2, 4096), (2, 4, 1, 1024), (2, 4, 1, 2048)):
             want.add((dt, d, mb, rs, kg, chunk))
         if d == 128:
             want |= {(dt, d, 2, 8, 1, 2048), (dt, d, 2, 8, 1, 4096)}
